@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Throughput of the GEMM hot path on one MI355X.
+
+A step is one call of prism_gemm(_batched) on the named synthetic workload with
+the operands already resident in HBM.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_TFLOPS = 2516.6      # dense bf16 / fp16 matrix peak of MI355X (256 CU x 4096 FLOP/clk x 2.4 GHz)
+PEAK_HBM_GBS = 8000.0
+ESIZE = {"bf16": 2, "f16": 2, "f32": 4}
+
+
+def algorithmic_bytes(w) -> float:
+    """Each operand read once, the result written once (plus the bias vector)."""
+    return w.batch * (w.M * w.K * 2 + w.K * w.N * 2 + w.M * w.N * ESIZE[w.c_dtype]) + (w.N * 4 if w.bias else 0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2_4096_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="output rows the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; --gpus must be 1 "
+              "(there is no multi-GPU path to measure)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2511_11939_amd as P
+    from workloads import CONFIGS, make_inputs
+
+    w = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    inp = make_inputs(w)
+    A = torch.from_numpy(inp["A"].view(np.int16)).cuda()
+    B = torch.from_numpy(inp["B"].view(np.int16)).cuda()
+    bias = None if inp["bias"] is None else torch.from_numpy(inp["bias"]).cuda()
+    C = torch.empty(w.batch * w.M * w.N, dtype=torch.float32 if w.c_dtype == "f32" else torch.int16,
+                    device="cuda")
+    desc = P.make_desc(ab_dtype=w.ab_dtype, c_dtype=w.c_dtype, layout_a=w.layout_a, layout_b=w.layout_b,
+                       alpha=w.alpha, bias=bias, split_k=w.split_k)
+    s, ws_bytes = P.prism_gemm_workspace_size(desc, w.M, w.N, w.K, w.batch)
+    assert s == 0
+    ws = None
+    if ws_bytes:
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        desc.workspace, desc.workspace_bytes = ws.data_ptr(), ws_bytes
+    s, plan = P.prism_gemm_plan(desc, w.M, w.N, w.K, A, w.lda(), w.M * w.K, B, w.ldb(), w.K * w.N,
+                                C, w.N, w.M * w.N, w.batch)
+    assert s == 0
+
+    stream = torch.cuda.current_stream()
+
+    def step():
+        P.gemm(A, B, C, M=w.M, N=w.N, K=w.K, desc=desc, batch=w.batch, strideA=w.M * w.K,
+               strideB=w.K * w.N, strideC=w.M * w.N, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = ev0.elapsed_time(ev1)                  # events on the launch stream
+
+    ms_per_step = wall * 1e3 / args.steps
+    tflops = w.flops / (ms_per_step * 1e-3) / 1e12
+    launch_ms = dev_ms / args.steps                 # average duration of one launch of the path
+    mfma_bound = w.name != "cfg5_batched_512"
+    if mfma_bound:
+        achieved = w.flops / (launch_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": None}
+    else:
+        achieved = algorithmic_bytes(w) / (launch_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined"}.get(plan.kernel, "none")
+    roofline["launch_us"] = round(launch_ms * 1e3, 2)
+
+    out = {
+        "metric": "bf16 GEMM TFLOP/s and % of MI355X dense bf16 MFMA peak (1 GPU)",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.ab_dtype == "bf16" else "f16", "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
+                   "layout": f"A {w.layout_a}, B {w.layout_b}, C row", "c_dtype": w.c_dtype,
+                   "tile": f"{plan.tile_m}x{plan.tile_n}x{plan.tile_k}", "waves": plan.waves,
+                   "split_k": plan.split_k, "workgroups": plan.workgroups},
+        "pct_of_mfma_peak": round(100.0 * tflops / PEAK_MFMA_TFLOPS, 2),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on an evenly spread subset of output rows of problem 0
+        from oracle import gemm_ref, oracle_threads, decode_output, check_against_oracle
+        n_rows = min(args.cpu_rows, w.M)
+        rows = np.unique(np.linspace(0, w.M - 1, n_rows).astype(np.int64))
+        t0 = time.perf_counter()
+        ref, mag = gemm_ref(inp["A"][0], inp["B"][0], ab_dtype=w.ab_dtype, M=w.M, N=w.N, K=w.K,
+                            layout_a=w.layout_a, layout_b=w.layout_b, alpha=w.alpha,
+                            bias=inp["bias"], rows=rows)
+        cpu_s = time.perf_counter() - t0
+        got = C.cpu().numpy()
+        got = got if w.c_dtype == "f32" else got.view(np.uint16)
+        got = got.reshape(w.batch, w.M, w.N)[0][rows]
+        res = check_against_oracle(decode_output(got, w.c_dtype), ref, mag, w.K, w.c_dtype)
+        out["cpu_baseline"] = {
+            "value": round(2.0 * rows.size * w.N * w.K / cpu_s / 1e12, 5), "unit": "TFLOP/s",
+            "cores": oracle_threads(), "kind": "oracle",
+            "sample": f"{rows.size} of {w.M} output rows x all {w.N} columns of problem 0, "
+                      f"{cpu_s:.2f} s wall",
+        }
+        out["parity_on_sample"] = {"ok": res["ok"], "max_err_over_bound": round(res["max_err_over_bound"], 4)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,13 @@
+"""MI355X (gfx950) dense GEMM library: Python binding of the C ABI in include/prism_gemm.h.
+
+Everything numeric runs in the HIP kernels of libprism_gemm.so; this package
+only marshals arguments.  There is no CPU fallback: without the built library
+every call raises.
+"""
+from .binding import (  # noqa: F401
+    GemmDesc, GemmPlan, PrismError, Status, DType, Layout,
+    load_library, library_path,
+    prism_gemm, prism_gemm_batched, prism_gemm_workspace_size, prism_gemm_plan,
+    prism_sched_map, prism_status_string, prism_version,
+    gemm, make_desc,
+)

@@ -1,0 +1,141 @@
+// Grid layer: which workgroup computes which output tile, and what happens to a
+// finished accumulator tile (scale, bias, conversion, store, or a split-K
+// partial).  The scheduler plays the part of the tile loop with super-tile
+// ordering in the paper's persistent hgemm kernel (code appendix, scheduler of
+// `my_h100_match_no_tail`); the alpha/beta epilogue is the paper's sgemm
+// epilogue (section 6.1) extended by a bias vector.
+#pragma once
+
+#include "lane.hpp"
+
+namespace prism {
+
+enum : int { DT_BF16 = 0, DT_F16 = 1, DT_F32 = 2 };
+
+// Problem as the kernels see it: C is row-major (a column-major C has been
+// turned into the transposed problem on the host), strides are in elements.
+struct GemmParams {
+    const char* A;        // element (m, k) at A + 2*(m*a_sm + k*a_sk)
+    const char* B;        // element (k, n) at B + 2*(n*b_sn + k*b_sk)
+    char* C;              // element (m, n) at C + esize*(m*ldc + n)
+    const float* bias;    // or nullptr
+    float* partial;       // split-K scratch [batch][split_k][M][N] fp32, or nullptr
+    int64_t a_sm, a_sk, b_sn, b_sk, ldc;
+    int64_t batch_a, batch_b, batch_c;
+    int M, N, K;
+    int batch, split_k, k_slice;   // k_slice: K extent of one slice, a multiple of 64
+    int tiles_m, tiles_n;
+    float alpha, beta;
+    int c_dtype;          // DT_*
+    int bias_along_m;     // 1 when the problem was transposed on the host
+    int a_vec, b_vec;     // operand is K-contiguous with 16-byte aligned rows / chunks
+    int c_vec;            // 4-element groups of C (and of the bias) are vector-aligned
+    int p_vec;            // 4-element groups of the split-K scratch are 16-byte aligned
+};
+
+namespace grid {
+
+constexpr int kDies = 8;        // accelerator dies (XCDs); workgroup ids are dealt round-robin
+constexpr int kGroupRows = 4;   // tile rows per super-tile group
+
+struct TileCoord {
+    int tile_m, tile_n, unit;
+};
+
+// Workgroup id -> (tile, unit).  Step 1 undoes the round-robin dealing so that
+// the workgroups resident on one die form a contiguous run of a tile order;
+// step 2 walks the tiles in groups of kGroupRows tile rows, m fastest, so that
+// such a run is a compact block sharing few A and B panels in that die's L2.
+__host__ __device__ inline TileCoord schedule(int wg, int tiles_m, int tiles_n, int units)
+{
+    const int tiles = tiles_m * tiles_n;
+    const int total = tiles * units;
+    const int per = (total + kDies - 1) / kDies;
+    int tall = total % kDies;
+    if (tall == 0) tall = kDies;
+    const int die = wg % kDies, local = wg / kDies;
+    const int q = die < tall ? die * per + local
+                             : tall * per + (die - tall) * (per - 1) + local;
+    TileCoord t;
+    t.unit = q / tiles;
+    const int r = q % tiles;
+    const int group_span = kGroupRows * tiles_n;
+    const int group = r / group_span;
+    const int first_m = group * kGroupRows;
+    const int rows = tiles_m - first_m < kGroupRows ? tiles_m - first_m : kGroupRows;
+    const int in_group = r % group_span;
+    t.tile_m = first_m + in_group % rows;
+    t.tile_n = in_group / rows;
+    return t;
+}
+
+// ---- epilogue ------------------------------------------------------------------------
+// Four accumulators of one lane: output row m, columns n0..n0+3.
+template <int OUT>  // DT_BF16 / DT_F16 / DT_F32
+__device__ __forceinline__ void finish4(const GemmParams& p, char* c_problem, int m, int n0, f32x4 v)
+{
+    if (m >= p.M || n0 >= p.N) return;
+    constexpr int esize = OUT == DT_F32 ? 4 : 2;
+    char* dst = c_problem + (static_cast<int64_t>(m) * p.ldc + n0) * esize;
+    const bool full = p.c_vec && (n0 + 3 < p.N);
+    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            bias[q] = p.bias_along_m ? p.bias[m] : (n0 + q < p.N ? p.bias[n0 + q] : 0.f);
+    }
+    float out[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) out[q] = p.alpha * v[q] + bias[q];
+    if (p.beta != 0.0f) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (n0 + q < p.N) {
+                float old;
+                if constexpr (OUT == DT_F32) old = reinterpret_cast<const float*>(dst)[q];
+                else if constexpr (OUT == DT_BF16) old = lane::from_bf16_bits(reinterpret_cast<const uint16_t*>(dst)[q]);
+                else old = lane::from_f16_bits(reinterpret_cast<const uint16_t*>(dst)[q]);
+                out[q] += p.beta * old;
+            }
+        }
+    }
+    if constexpr (OUT == DT_F32) {
+        if (full) {
+            *reinterpret_cast<f32x4*>(dst) = f32x4{out[0], out[1], out[2], out[3]};
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (n0 + q < p.N) reinterpret_cast<float*>(dst)[q] = out[q];
+        }
+    } else {
+        uint16_t h[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            h[q] = OUT == DT_BF16 ? lane::to_bf16_bits(out[q]) : lane::to_f16_bits(out[q]);
+        if (full) {
+            *reinterpret_cast<u32x2*>(dst) = u32x2{static_cast<uint32_t>(h[0]) | (static_cast<uint32_t>(h[1]) << 16),
+                                                  static_cast<uint32_t>(h[2]) | (static_cast<uint32_t>(h[3]) << 16)};
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (n0 + q < p.N) reinterpret_cast<uint16_t*>(dst)[q] = h[q];
+        }
+    }
+}
+
+// Raw fp32 partial sums of one K slice.
+__device__ __forceinline__ void partial4(const GemmParams& p, float* slab, int m, int n0, f32x4 v)
+{
+    if (m >= p.M || n0 >= p.N) return;
+    float* dst = slab + static_cast<int64_t>(m) * p.N + n0;
+    if (p.p_vec && (n0 + 3 < p.N)) {
+        *reinterpret_cast<f32x4*>(dst) = v;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (n0 + q < p.N) dst[q] = v[q];
+    }
+}
+
+}  // namespace grid
+}  // namespace prism

@@ -1,0 +1,300 @@
+// Host side of the C ABI: argument validation, the choice of kernel, tile shape
+// and K split, and the launches.  No arithmetic of the matrix product happens
+// here; everything numeric runs in the device kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/prism_gemm.h"
+#include "grid.hpp"
+#include "launch.hpp"
+
+namespace {
+
+using prism::GemmParams;
+
+constexpr int kComputeUnits = 256;
+constexpr int kMaxSplit = 64;
+constexpr int64_t kIntMax = 2147483647;
+
+struct Problem {
+    GemmParams p;
+    prism_gemm_plan_t plan;
+    int ab_dtype;
+    int pipe_config;  // index into kPipeConfigs when plan.kernel == 2
+};
+
+bool valid_dtype_ab(int v) { return v == PRISM_DTYPE_BF16 || v == PRISM_DTYPE_F16; }
+bool valid_dtype_c(int v) { return v == PRISM_DTYPE_BF16 || v == PRISM_DTYPE_F16 || v == PRISM_DTYPE_F32; }
+bool valid_layout(int v) { return v == PRISM_ROW_MAJOR || v == PRISM_COL_MAJOR; }
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Elements spanned by a rows x cols matrix with leading dimension ld.
+int64_t span(int layout, int64_t rows, int64_t cols, int64_t ld)
+{
+    if (rows == 0 || cols == 0) return 0;
+    return layout == PRISM_ROW_MAJOR ? (rows - 1) * ld + cols : (cols - 1) * ld + rows;
+}
+
+bool overlaps(const void* a, int64_t a_bytes, const void* b, int64_t b_bytes)
+{
+    if (!a || !b || a_bytes <= 0 || b_bytes <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + static_cast<uintptr_t>(b_bytes) && b0 < a0 + static_cast<uintptr_t>(a_bytes);
+}
+
+int forced_pipe_config()
+{
+    // Experiment hook: PRISM_GEMM_CONFIG=<index> pins the pipeline tile configuration.
+    const char* e = std::getenv("PRISM_GEMM_CONFIG");
+    if (!e || !*e) return -1;
+    const int v = std::atoi(e);
+    return v >= 0 && v < prism::kNumPipeConfigs ? v : -1;
+}
+
+// Validates everything, normalises to a row-major C and chooses the launch.
+prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,
+                            const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb,
+                            int64_t strideB, const void* C, int64_t ldc, int64_t strideC, int64_t batch,
+                            bool need_pointers, Problem* out)
+{
+    if (!d || !out) return PRISM_ERR_INVALID_ARG;
+    if (!valid_dtype_ab(d->ab_dtype) || !valid_dtype_c(d->c_dtype) || !valid_layout(d->layout_a) ||
+        !valid_layout(d->layout_b) || !valid_layout(d->layout_c))
+        return PRISM_ERR_UNSUPPORTED;
+    if (d->reserved != 0) return PRISM_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || batch < 0 || d->split_k < 0) return PRISM_ERR_INVALID_ARG;
+    if (M > kIntMax || N > kIntMax || K > kIntMax - 64 || batch > kIntMax) return PRISM_ERR_INVALID_ARG;
+    if (lda < 1 || ldb < 1 || ldc < 1) return PRISM_ERR_INVALID_ARG;
+    if (lda < (d->layout_a == PRISM_ROW_MAJOR ? K : M)) return PRISM_ERR_INVALID_ARG;
+    if (ldb < (d->layout_b == PRISM_ROW_MAJOR ? N : K)) return PRISM_ERR_INVALID_ARG;
+    if (ldc < (d->layout_c == PRISM_ROW_MAJOR ? N : M)) return PRISM_ERR_INVALID_ARG;
+    if (!(d->alpha == d->alpha) || !(d->beta == d->beta)) return PRISM_ERR_INVALID_ARG;  // NaN scales
+
+    std::memset(out, 0, sizeof(*out));
+    prism_gemm_plan_t& plan = out->plan;
+    plan.split_k = 1;
+    const bool empty = M == 0 || N == 0 || batch == 0;
+    if (empty) return PRISM_OK;  // plan.kernel == 0: nothing to do
+
+    const int64_t c_span = span(d->layout_c, M, N, ldc);
+    const int64_t a_span = span(d->layout_a, M, K, lda), b_span = span(d->layout_b, K, N, ldb);
+    const int c_esize = d->c_dtype == PRISM_DTYPE_F32 ? 4 : 2;
+    if (need_pointers) {
+        if (!C || (K > 0 && (!A || !B))) return PRISM_ERR_INVALID_ARG;
+    }
+    if (batch > 1) {
+        const int64_t sc = strideC < 0 ? -strideC : strideC;
+        if (sc < c_span) return PRISM_ERR_INVALID_ARG;  // C matrices of the batch would overlap
+    }
+    if (batch == 1 || (strideA >= 0 && strideB >= 0 && strideC >= 0)) {
+        // C must not share memory with A or B (checked over the whole batch extent)
+        const int64_t nb = batch - 1;
+        const int64_t c_bytes = (nb * strideC + c_span) * c_esize;
+        if (overlaps(C, c_bytes, A, (nb * strideA + a_span) * 2) ||
+            overlaps(C, c_bytes, B, (nb * strideB + b_span) * 2))
+            return PRISM_ERR_INVALID_ARG;
+    }
+
+    // ---- normalise: a column-major C is the row-major C^T = B^T A^T
+    GemmParams& p = out->p;
+    int64_t a_sm = d->layout_a == PRISM_ROW_MAJOR ? lda : 1, a_sk = d->layout_a == PRISM_ROW_MAJOR ? 1 : lda;
+    int64_t b_sk = d->layout_b == PRISM_ROW_MAJOR ? ldb : 1, b_sn = d->layout_b == PRISM_ROW_MAJOR ? 1 : ldb;
+    if (d->layout_c == PRISM_COL_MAJOR) {
+        plan.swapped = 1;
+        p.A = static_cast<const char*>(B); p.a_sm = b_sn; p.a_sk = b_sk; p.batch_a = strideB;
+        p.B = static_cast<const char*>(A); p.b_sn = a_sm; p.b_sk = a_sk; p.batch_b = strideA;
+        p.M = static_cast<int>(N); p.N = static_cast<int>(M);
+        p.bias_along_m = 1;
+    } else {
+        p.A = static_cast<const char*>(A); p.a_sm = a_sm; p.a_sk = a_sk; p.batch_a = strideA;
+        p.B = static_cast<const char*>(B); p.b_sn = b_sn; p.b_sk = b_sk; p.batch_b = strideB;
+        p.M = static_cast<int>(M); p.N = static_cast<int>(N);
+        p.bias_along_m = 0;
+    }
+    p.K = static_cast<int>(K);
+    p.C = static_cast<char*>(const_cast<void*>(C));
+    p.ldc = ldc;
+    p.batch_c = strideC;
+    p.batch = static_cast<int>(batch);
+    p.bias = d->bias;
+    p.alpha = d->alpha;
+    p.beta = d->beta;
+    p.c_dtype = d->c_dtype;
+    out->ab_dtype = d->ab_dtype;
+
+    // ---- alignment facts
+    const bool a_kfast = p.a_sk == 1, b_kfast = p.b_sk == 1;
+    p.a_vec = a_kfast && aligned(p.A, 16) && p.a_sm % 8 == 0 && (p.batch == 1 || p.batch_a % 8 == 0);
+    p.b_vec = b_kfast && aligned(p.B, 16) && p.b_sn % 8 == 0 && (p.batch == 1 || p.batch_b % 8 == 0);
+    const size_t c_align = 4 * static_cast<size_t>(c_esize);
+    p.c_vec = aligned(p.C, c_align) && p.ldc % 4 == 0 && (p.batch == 1 || p.batch_c % 4 == 0) &&
+              (!p.bias || p.bias_along_m || aligned(p.bias, 4));
+    p.p_vec = p.N % 4 == 0 && aligned(d->workspace, 16);
+
+    if (K == 0) {  // C <- bias + beta*C: only the epilogue kernel runs
+        plan.kernel = 0;
+        p.split_k = 0;
+        p.tiles_m = p.tiles_n = 0;
+        return PRISM_OK;
+    }
+
+    // ---- kernel and tile shape
+    const int64_t ksteps = ceil_div(K, 64);
+    const bool pipe_ok = p.a_vec && p.b_vec && K % 64 == 0 && p.a_sm < (int64_t{1} << 21) &&
+                         p.b_sn < (int64_t{1} << 21);
+    int tile_m = prism::kStagedTileM, tile_n = prism::kStagedTileN, waves = prism::kStagedWaves;
+    plan.kernel = 1;
+    if (pipe_ok) {
+        plan.kernel = 2;
+        int cfg = forced_pipe_config();
+        if (cfg < 0) {
+            // Big tiles when they still give most compute units a workgroup, else small ones.
+            const int64_t big = ceil_div(p.M, 256) * ceil_div(p.N, 256) * batch;
+            cfg = (big >= kComputeUnits / 2 || (p.M >= 512 && p.N >= 512)) ? 0 : 2;
+        }
+        out->pipe_config = cfg;
+        tile_m = prism::kPipeConfigs[cfg].tile_m;
+        tile_n = prism::kPipeConfigs[cfg].tile_n;
+        waves = prism::kPipeConfigs[cfg].waves;
+    }
+    const int64_t tiles_m = ceil_div(p.M, tile_m), tiles_n = ceil_div(p.N, tile_n);
+    if (tiles_m * tiles_n > kIntMax / 64 || tiles_m * tiles_n * batch > kIntMax / 64) return PRISM_ERR_INVALID_ARG;
+
+    // ---- K split: explicit request, or enough slices to give every compute unit a workgroup
+    int64_t want = d->split_k;
+    const int64_t units = tiles_m * tiles_n * batch;
+    const size_t slab_bytes = static_cast<size_t>(batch) * p.M * p.N * sizeof(float);
+    if (want == 0) {
+        want = 1;
+        if (units * 2 <= kComputeUnits && ksteps >= 8) {
+            want = kComputeUnits / units;
+            if (want > ksteps / 4) want = ksteps / 4;  // at least four K steps per slice
+            if (want > kMaxSplit) want = kMaxSplit;
+            if (want < 1) want = 1;
+        }
+    }
+    if (want > ksteps) want = ksteps;
+    int64_t slice_steps = ceil_div(ksteps, want);
+    int64_t split = ceil_div(ksteps, slice_steps);  // no empty slices
+    size_t ws_need = split > 1 ? slab_bytes * static_cast<size_t>(split) : 0;
+    if (split > 1 && need_pointers && (!d->workspace || d->workspace_bytes < ws_need)) {
+        if (d->split_k > 1) return PRISM_ERR_WORKSPACE;
+        split = 1; slice_steps = ksteps; ws_need = 0;  // library's own choice: fall back quietly
+    }
+    p.split_k = static_cast<int>(split);
+    p.k_slice = static_cast<int>(slice_steps * 64);
+    p.partial = split > 1 ? static_cast<float*>(d->workspace) : nullptr;
+    p.tiles_m = static_cast<int>(tiles_m);
+    p.tiles_n = static_cast<int>(tiles_n);
+
+    plan.tile_m = tile_m; plan.tile_n = tile_n; plan.tile_k = 64; plan.waves = waves;
+    plan.split_k = static_cast<int32_t>(split);
+    plan.tiles_m = tiles_m; plan.tiles_n = tiles_n;
+    plan.workgroups = units * split;
+    plan.workspace_bytes = ws_need;
+    if (plan.workgroups > kIntMax) return PRISM_ERR_INVALID_ARG;
+    return PRISM_OK;
+}
+
+prism_status_t run(const Problem& pr, hipStream_t stream)
+{
+    const GemmParams& p = pr.p;
+    if (p.M == 0 || p.N == 0 || p.batch == 0) return PRISM_OK;
+    hipError_t e = hipSuccess;
+    if (pr.plan.kernel == 2)
+        e = prism::launch_pipelined(pr.pipe_config, pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);
+    else if (pr.plan.kernel == 1)
+        e = prism::launch_staged(pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);
+    if (e != hipSuccess) return PRISM_ERR_LAUNCH;
+    if (p.split_k != 1) {  // K == 0 (split_k == 0) or a real split: the reduction writes C
+        e = prism::launch_reduce(p, stream);
+        if (e != hipSuccess) return PRISM_ERR_LAUNCH;
+    }
+    return PRISM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+prism_status_t prism_gemm_batched(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,
+                                  const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb,
+                                  int64_t strideB, void* C, int64_t ldc, int64_t strideC, int64_t batch,
+                                  void* hip_stream)
+{
+    Problem pr;
+    const prism_status_t s =
+        make_problem(d, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch, true, &pr);
+    if (s != PRISM_OK) return s;
+    return run(pr, static_cast<hipStream_t>(hip_stream));
+}
+
+prism_status_t prism_gemm(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K, const void* A,
+                          int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, void* hip_stream)
+{
+    return prism_gemm_batched(d, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, 1, hip_stream);
+}
+
+prism_status_t prism_gemm_plan(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K, const void* A,
+                               int64_t lda, int64_t strideA, const void* B, int64_t ldb, int64_t strideB,
+                               const void* C, int64_t ldc, int64_t strideC, int64_t batch,
+                               prism_gemm_plan_t* plan_out)
+{
+    if (!plan_out) return PRISM_ERR_INVALID_ARG;
+    Problem pr;
+    const prism_status_t s =
+        make_problem(d, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch, false, &pr);
+    if (s != PRISM_OK) return s;
+    *plan_out = pr.plan;
+    return PRISM_OK;
+}
+
+prism_status_t prism_gemm_workspace_size(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,
+                                         int64_t batch, size_t* bytes_out)
+{
+    if (!d || !bytes_out) return PRISM_ERR_INVALID_ARG;
+    // Leading dimensions and strides do not influence the split; use the packed ones.
+    const int64_t lda = d->layout_a == PRISM_ROW_MAJOR ? K : M, ldb = d->layout_b == PRISM_ROW_MAJOR ? N : K;
+    const int64_t ldc = d->layout_c == PRISM_ROW_MAJOR ? N : M;
+    Problem pr;
+    const prism_status_t s =
+        make_problem(d, M, N, K, nullptr, lda < 1 ? 1 : lda, M * K, nullptr, ldb < 1 ? 1 : ldb, K * N, nullptr,
+                     ldc < 1 ? 1 : ldc, M * N, batch, false, &pr);
+    if (s != PRISM_OK) return s;
+    *bytes_out = pr.plan.workspace_bytes;
+    return PRISM_OK;
+}
+
+prism_status_t prism_sched_map(int64_t wg, int64_t tiles_m, int64_t tiles_n, int64_t units, int64_t* tile_m,
+                               int64_t* tile_n, int64_t* unit)
+{
+    if (!tile_m || !tile_n || !unit || tiles_m < 1 || tiles_n < 1 || units < 1) return PRISM_ERR_INVALID_ARG;
+    if (tiles_m > kIntMax || tiles_n > kIntMax || units > kIntMax) return PRISM_ERR_INVALID_ARG;
+    if (tiles_m * tiles_n > kIntMax || tiles_m * tiles_n * units > kIntMax) return PRISM_ERR_INVALID_ARG;
+    if (wg < 0 || wg >= tiles_m * tiles_n * units) return PRISM_ERR_INVALID_ARG;
+    const prism::grid::TileCoord c = prism::grid::schedule(static_cast<int>(wg), static_cast<int>(tiles_m),
+                                                           static_cast<int>(tiles_n), static_cast<int>(units));
+    *tile_m = c.tile_m;
+    *tile_n = c.tile_n;
+    *unit = c.unit;
+    return PRISM_OK;
+}
+
+const char* prism_status_string(prism_status_t s)
+{
+    switch (s) {
+    case PRISM_OK: return "PRISM_OK";
+    case PRISM_ERR_INVALID_ARG: return "PRISM_ERR_INVALID_ARG";
+    case PRISM_ERR_UNSUPPORTED: return "PRISM_ERR_UNSUPPORTED";
+    case PRISM_ERR_WORKSPACE: return "PRISM_ERR_WORKSPACE";
+    case PRISM_ERR_LAUNCH: return "PRISM_ERR_LAUNCH";
+    }
+    return "PRISM_ERR_UNKNOWN";
+}
+
+int prism_version(void) { return 100; }
+
+}  // extern "C"

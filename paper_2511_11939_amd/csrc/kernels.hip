@@ -1,0 +1,195 @@
+// Device kernels: thin __global__ shells that place a workgroup on its tile
+// (grid layer), run a workgroup main loop and hand the accumulators to the
+// epilogue.  All arithmetic of the matrix product happens here on the GPU.
+#include <hip/hip_runtime.h>
+
+#include "grid.hpp"
+#include "lane.hpp"
+#include "launch.hpp"
+#include "wave.hpp"
+#include "workgroup.hpp"
+
+namespace prism {
+
+const PipeConfig kPipeConfigs[kNumPipeConfigs] = {
+    {0, 256, 256, 4, 2, "256x256x64_w4_s2"},
+    {1, 256, 256, 8, 2, "256x256x64_w8_s2"},
+    {2, 128, 128, 4, 3, "128x128x64_w4_s3"},
+};
+
+namespace {
+
+struct Placement {
+    int batch, slice, m0, n0, k_begin, k_end;
+};
+
+template <int BM, int BN>
+__device__ __forceinline__ Placement place(const GemmParams& p, int wg)
+{
+    const grid::TileCoord c = grid::schedule(wg, p.tiles_m, p.tiles_n, p.batch * p.split_k);
+    Placement q;
+    q.batch = c.unit / p.split_k;
+    q.slice = c.unit - q.batch * p.split_k;
+    q.m0 = c.tile_m * BM;
+    q.n0 = c.tile_n * BN;
+    q.k_begin = q.slice * p.k_slice;
+    q.k_end = q.k_begin + p.k_slice < p.K ? q.k_begin + p.k_slice : p.K;
+    return q;
+}
+
+// Accumulators of one wave tile -> C or the split-K scratch.  Workgroup-collective:
+// every wave must call it (it starts with a barrier that retires the operand slots).
+template <typename TileT, int MT, int NT>
+__device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q, const TileT& acc,
+                                         int m_wave, int n_wave, char* lds, int wave, int lane)
+{
+    __syncthreads();
+    char* patch = lds + wave * wg::drain_patch_bytes(NT);
+    if (p.split_k > 1) {
+        float* slab = p.partial + (static_cast<int64_t>(q.batch) * p.split_k + q.slice) * p.M * p.N;
+        wg::drain<MT, NT>(acc, patch, lane,
+                          [&](int r, int c, f32x4 v) { grid::partial4(p, slab, m_wave + r, n_wave + c, v); });
+        return;
+    }
+    const int esize = p.c_dtype == DT_F32 ? 4 : 2;
+    char* c_problem = p.C + static_cast<int64_t>(q.batch) * p.batch_c * esize;
+    if (p.c_dtype == DT_BF16)
+        wg::drain<MT, NT>(acc, patch, lane, [&](int r, int c, f32x4 v) {
+            grid::finish4<DT_BF16>(p, c_problem, m_wave + r, n_wave + c, v);
+        });
+    else if (p.c_dtype == DT_F16)
+        wg::drain<MT, NT>(acc, patch, lane, [&](int r, int c, f32x4 v) {
+            grid::finish4<DT_F16>(p, c_problem, m_wave + r, n_wave + c, v);
+        });
+    else
+        wg::drain<MT, NT>(acc, patch, lane, [&](int r, int c, f32x4 v) {
+            grid::finish4<DT_F32>(p, c_problem, m_wave + r, n_wave + c, v);
+        });
+}
+
+template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_pipelined(const GemmParams p)
+{
+    using P = wg::Pipeline<T, BM, BN, WAVES_M, WAVES_N, STAGES>;
+    __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Placement q = place<BM, BN>(p, blockIdx.x);
+
+    const char* a_tile = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm + q.k_begin);
+    const char* b_tile = p.B + 2 * (q.batch * p.batch_b + q.n0 * p.b_sn + q.k_begin);
+    const int a_rows = p.M - q.m0 < BM ? p.M - q.m0 : BM;
+    const int b_rows = p.N - q.n0 < BN ? p.N - q.n0 : BN;
+
+    typename P::tile_t acc;
+    acc.clear();
+    P::run(acc, a_tile, static_cast<uint32_t>(2 * p.a_sm), a_rows, b_tile, static_cast<uint32_t>(2 * p.b_sn),
+           b_rows, (q.k_end - q.k_begin) / lane::kTileK, lds, wave, lane);
+
+    epilogue<typename P::tile_t, P::MT, P::NT>(p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
+                                               q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_staged(const GemmParams p)
+{
+    using S = wg::Staged<T>;
+    __shared__ __attribute__((aligned(1024))) char lds[S::LDS_BYTES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Placement q = place<S::BM, S::BN>(p, blockIdx.x);
+
+    const char* a_tile = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm);
+    const char* b_tile = p.B + 2 * (q.batch * p.batch_b + q.n0 * p.b_sn);
+    const int a_rows = p.M - q.m0 < S::BM ? p.M - q.m0 : S::BM;
+    const int b_rows = p.N - q.n0 < S::BN ? p.N - q.n0 : S::BN;
+
+    typename S::tile_t acc;
+    acc.clear();
+    S::run(acc, a_tile, p.a_sm, p.a_sk, a_rows, p.a_vec != 0, b_tile, p.b_sn, p.b_sk, b_rows, p.b_vec != 0,
+           q.k_begin, q.k_end, lds, wave, lane);
+
+    epilogue<typename S::tile_t, S::MT, S::NT>(p, q, acc, q.m0 + (wave >> 1) * S::WTM,
+                                               q.n0 + (wave & 1) * S::WTN, lds, wave, lane);
+}
+
+// One thread per group of four consecutive n.  Slices are added in order
+// 0, 1, ..., split_k-1 so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void splitk_reduce(const GemmParams p)
+{
+    const int groups_n = (p.N + 3) / 4;
+    const int64_t total = static_cast<int64_t>(p.batch) * p.M * groups_n;
+    const int64_t slab = static_cast<int64_t>(p.M) * p.N;
+    for (int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; idx < total;
+         idx += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const int g = static_cast<int>(idx % groups_n);
+        const int64_t bm = idx / groups_n;
+        const int m = static_cast<int>(bm % p.M);
+        const int b = static_cast<int>(bm / p.M);
+        const int n0 = 4 * g;
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        const float* src = p.partial + static_cast<int64_t>(b) * p.split_k * slab + static_cast<int64_t>(m) * p.N + n0;
+        for (int s = 0; s < p.split_k; ++s, src += slab) {
+            if (p.p_vec && n0 + 3 < p.N) {
+                sum += *reinterpret_cast<const f32x4*>(src);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n0 + e < p.N) sum[e] += src[e];
+            }
+        }
+        const int esize = p.c_dtype == DT_F32 ? 4 : 2;
+        char* c_problem = p.C + static_cast<int64_t>(b) * p.batch_c * esize;
+        if (p.c_dtype == DT_BF16) grid::finish4<DT_BF16>(p, c_problem, m, n0, sum);
+        else if (p.c_dtype == DT_F16) grid::finish4<DT_F16>(p, c_problem, m, n0, sum);
+        else grid::finish4<DT_F32>(p, c_problem, m, n0, sum);
+    }
+}
+
+template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+hipError_t launch_pipe(const GemmParams& p, int workgroups, hipStream_t stream)
+{
+    hipLaunchKernelGGL((gemm_pipelined<T, BM, BN, WAVES_M, WAVES_N, STAGES>), dim3(workgroups),
+                       dim3(WAVES_M * WAVES_N * 64), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_pipe_config(int config, const GemmParams& p, int workgroups, hipStream_t stream)
+{
+    switch (config) {
+    case 0: return launch_pipe<T, 256, 256, 2, 2, 2>(p, workgroups, stream);
+    case 1: return launch_pipe<T, 256, 256, 2, 4, 2>(p, workgroups, stream);
+    case 2: return launch_pipe<T, 128, 128, 2, 2, 3>(p, workgroups, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream)
+{
+    return ab_dtype == DT_BF16 ? launch_pipe_config<bf16_t>(config, p, workgroups, stream)
+                               : launch_pipe_config<f16_t>(config, p, workgroups, stream);
+}
+
+hipError_t launch_staged(int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream)
+{
+    if (ab_dtype == DT_BF16)
+        hipLaunchKernelGGL(gemm_staged<bf16_t>, dim3(workgroups), dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(gemm_staged<f16_t>, dim3(workgroups), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce(const GemmParams& p, hipStream_t stream)
+{
+    const int64_t total = static_cast<int64_t>(p.batch) * p.M * ((p.N + 3) / 4);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(splitk_reduce, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace prism

@@ -1,0 +1,89 @@
+// Lane layer: what ONE lane of a wavefront does on its own.
+//
+// Every function here is written from the point of view of a single lane and
+// receives that lane's index inside its wavefront (0..63) as an argument; it
+// never looks at workgroup or grid coordinates.  This mirrors the paper's
+// rule that a function is written at, and callable only at, one granularity
+// (perspectives, section 3.2; the thread-level fragment loads of its
+// `simple_mma` device function are the counterpart of load_fragment below).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace prism {
+
+using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
+using f16x8 = __attribute__((ext_vector_type(8))) _Float16;
+using f32x16 = __attribute__((ext_vector_type(16))) float;
+using f32x4 = __attribute__((ext_vector_type(4))) float;
+using u32x4 = __attribute__((ext_vector_type(4))) uint32_t;
+using u32x2 = __attribute__((ext_vector_type(2))) uint32_t;
+
+struct bf16_t {};  // operand tags
+struct f16_t {};
+
+template <typename T> struct Frag;
+template <> struct Frag<bf16_t> { using type = bf16x8; };
+template <> struct Frag<f16_t> { using type = f16x8; };
+
+namespace lane {
+
+// ---- LDS tile layout ---------------------------------------------------------
+// An operand tile in LDS is `rows` x 64 elements, K contiguous: 128 bytes per
+// row, i.e. eight 16-byte chunks.  Chunk c of row r is kept at chunk position
+// c ^ swizzle(r).  With the swizzle below, 16 lanes that read the same logical
+// chunk of 16 consecutive rows touch 16 distinct 16-byte bank groups of a
+// 256-byte LDS row, and 8 consecutive rows touch 8 distinct groups of a
+// 128-byte row, so the 128-bit fragment reads are conflict free.
+constexpr int kTileK = 64;          // elements per tile row
+constexpr int kRowBytes = kTileK * 2;
+constexpr int kChunkBytes = 16;
+constexpr int kChunksPerRow = kRowBytes / kChunkBytes;
+
+__host__ __device__ constexpr int swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+__host__ __device__ constexpr int tile_offset(int row, int chunk)
+{
+    return row * kRowBytes + ((chunk ^ swizzle(row)) * kChunkBytes);
+}
+
+// One lane's share of a 32-row x 16-k MFMA operand fragment: 8 consecutive k
+// of row (row0 + lane%32), taken from k-chunk (2*ksub + lane/32) of the tile.
+template <typename T>
+__device__ __forceinline__ typename Frag<T>::type
+load_fragment(const char* tile, int row0, int ksub, int lane)
+{
+    const int row = row0 + (lane & 31);
+    const int chunk = 2 * ksub + (lane >> 5);
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(tile + tile_offset(row, chunk));
+    return __builtin_bit_cast(typename Frag<T>::type, raw);
+}
+
+// ---- accumulator layout of the 32x32 MFMA -----------------------------------------
+// With the fragment of the "row" operand r and the "column" operand c,
+// D = r * c^T is spread so that lane l holds column l%32 and, in register i
+// (0..15), row 8*(i/4) + 4*(l/32) + i%4.
+__host__ __device__ constexpr int acc_row(int reg, int lane) { return 8 * (reg >> 2) + 4 * (lane >> 5) + (reg & 3); }
+__host__ __device__ constexpr int acc_col(int lane) { return lane & 31; }
+
+// ---- output conversion ---------------------------------------------------------
+__device__ __forceinline__ uint16_t to_bf16_bits(float x)
+{
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));  // round to nearest even
+}
+__device__ __forceinline__ uint16_t to_f16_bits(float x)
+{
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(x));  // round to nearest even
+}
+__device__ __forceinline__ float from_bf16_bits(uint16_t h)
+{
+    return __builtin_bit_cast(float, static_cast<uint32_t>(h) << 16);
+}
+__device__ __forceinline__ float from_f16_bits(uint16_t h)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, h));
+}
+
+}  // namespace lane
+}  // namespace prism

@@ -1,0 +1,29 @@
+// Host-visible launchers of the device kernels (defined in kernels.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "grid.hpp"
+
+namespace prism {
+
+// Workgroup-tile configurations of the direct-to-LDS pipeline.
+struct PipeConfig {
+    int id;
+    int tile_m, tile_n, waves, stages;
+    const char* name;
+};
+constexpr int kNumPipeConfigs = 3;
+extern const PipeConfig kPipeConfigs[kNumPipeConfigs];
+
+constexpr int kStagedTileM = 128, kStagedTileN = 128, kStagedWaves = 4;
+
+// Each returns the launch error of the HIP runtime (hipSuccess when accepted).
+// `workgroups` = p.tiles_m * p.tiles_n * p.batch * p.split_k.
+hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream);
+hipError_t launch_staged(int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream);
+// Sums the split_k partial slabs in slice order and applies the epilogue; with
+// p.split_k == 0 it writes C <- bias + beta*C (the K == 0 case).
+hipError_t launch_reduce(const GemmParams& p, hipStream_t stream);
+
+}  // namespace prism

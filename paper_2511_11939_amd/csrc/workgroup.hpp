@@ -1,0 +1,291 @@
+// Workgroup layer: everything the wavefronts of one workgroup do together --
+// moving operand tiles from global memory into LDS, the barriers that order
+// those moves against the fragment reads, and the K loop around the wave
+// tiles.  Functions take the calling wave's index inside the workgroup and the
+// lane's index inside the wave; they never look at grid coordinates.
+//
+// The structure follows what the paper says a peak-rate matrix multiply needs
+// (section 6.2): data movement pipelined under the matrix instructions with
+// statically sized, individually synchronised pipeline slots.  On gfx950 the
+// asynchronous copy is the direct global->LDS load and the slot hand-over is
+// one workgroup barrier per K step, placed by hand where the paper's compiler
+// would insert it (section 5, synchronisation at loop back-edges).
+#pragma once
+
+#include "lane.hpp"
+#include "wave.hpp"
+
+namespace prism {
+namespace wg {
+
+// s_waitcnt immediate for gfx9-family encodings: at most `vm` vector-memory and
+// `lgkm` LDS/scalar operations of this wave may still be outstanding.
+constexpr int waitcnt_imm(int vm, int lgkm)
+{
+    return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 15) << 8);
+}
+template <int VM, int LGKM>
+__device__ __forceinline__ void wait_counts()
+{
+    static_assert(VM >= 0 && VM <= 63 && LGKM >= 0 && LGKM <= 15, "counter out of range");
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM, LGKM));
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p)
+{
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) char*)p));
+}
+
+// Asynchronous 16-bytes-per-lane copy global -> LDS for one wavefront: lane l
+// reads 16 bytes at (uniform_base + lane_offset) and the hardware deposits them
+// at lds_addr + 16*l.  The wave's vector-memory counter tracks completion.
+__device__ __forceinline__ const char* scalarize(const char* p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+__device__ __forceinline__ void copy_async_16(const char* uniform_base, uint32_t lane_offset,
+                                              uint32_t lds_addr)
+{
+    uniform_base = scalarize(uniform_base);  // no-ops when the values already live in SGPRs
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_addr)
+                 : "memory");
+}
+
+// Drains one wave's accumulator tile through a private LDS patch so that the
+// values leave the wave as runs of four consecutive n, whole rows at a time
+// (the MFMA leaves each lane with values of 32 different rows).  `patch` must
+// hold kDrainRows x (32*NT + 4) floats, is used by this wave only, and must
+// not be in use by anybody else (barrier before the first call).
+// sink(row_in_wave_tile, col_in_wave_tile, f32x4) receives every group once.
+constexpr int kDrainRows = 32;
+constexpr int drain_patch_bytes(int nt) { return kDrainRows * (32 * nt + 4) * 4; }
+
+template <int MT, int NT, typename TileT, typename Sink>
+__device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, Sink&& sink)
+{
+    constexpr int WTN = 32 * NT;
+    constexpr int PITCH = WTN + 4;  // floats; +4 shifts consecutive rows by one 16-byte bank group
+    constexpr int LANES_PER_ROW = WTN / 4;
+    constexpr int ROWS_PER_ITER = 64 / LANES_PER_ROW;
+    constexpr int ITERS = kDrainRows / ROWS_PER_ITER;
+    float* buf = reinterpret_cast<float*>(patch);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        float* wr = buf + lane::acc_col(lane) * PITCH;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x16& a = acc.acc[i][j];
+                *reinterpret_cast<f32x4*>(wr + 32 * j + lane::acc_row(4 * g, lane)) =
+                    f32x4{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
+            }
+        const int col = 4 * (lane % LANES_PER_ROW);
+#pragma unroll 4
+        for (int it = 0; it < ITERS; ++it) {
+            const int row = it * ROWS_PER_ITER + lane / LANES_PER_ROW;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(buf + row * PITCH + col);
+            sink(32 * i + row, col, v);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Pipelined main loop: K-contiguous operands, direct-to-LDS copies, STAGES slots.
+// ------------------------------------------------------------------------------------
+template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+struct Pipeline {
+    static constexpr int NW = WAVES_M * WAVES_N;
+    static constexpr int THREADS = NW * 64;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    static constexpr int MT = WTM / 32, NT = WTN / 32;
+    static constexpr int KSUB = lane::kTileK / 16;
+    static constexpr int A_BYTES = BM * lane::kRowBytes, B_BYTES = BN * lane::kRowBytes;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int A_COPIES = BM / 8 / NW, B_COPIES = BN / 8 / NW;  // per wave per K step
+    static constexpr int COPIES = A_COPIES + B_COPIES;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
+    static_assert(NW % 2 == 0, "row-block parity must be a per-wave constant");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
+    static_assert(LDS_BYTES <= 163840, "LDS budget of one gfx950 compute unit");
+    static_assert(NW * drain_patch_bytes(NT) <= LDS_BYTES, "epilogue patches reuse the operand slots");
+    static_assert(STAGES >= 2 && (STAGES - 1) * COPIES <= 63, "vmcnt range");
+
+    using tile_t = wave::Tile<T, MT, NT>;
+    using frag_t = typename Frag<T>::type;
+
+    // a_tile / b_tile: uniform byte pointers to element (first row of the tile,
+    // first k of the slice); a_ld / b_ld: row pitch in bytes; a_rows / b_rows:
+    // rows of the tile that exist (>= 1; missing rows re-read the last one and
+    // their results are never stored).  ksteps >= 1 steps of 64 k each.
+    __device__ __forceinline__ static void run(tile_t& acc, const char* a_tile, uint32_t a_ld, int a_rows,
+                               const char* b_tile, uint32_t b_ld, int b_rows, int ksteps,
+                               char* lds, int wave, int lane)
+    {
+        // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave), 8 rows x 8 chunks;
+        //    lane l fills chunk position l%8 of row l/8 with the logical chunk the swizzle wants.
+        const int sub_row = lane >> 3;
+        const int chunk = (lane & 7) ^ lane::swizzle(8 * (wave & 1) + sub_row);
+        uint32_t a_off[A_COPIES], b_off[B_COPIES];
+#pragma unroll
+        for (int i = 0; i < A_COPIES; ++i) {
+            int row = (i * NW + wave) * 8 + sub_row;
+            row = row < a_rows ? row : a_rows - 1;
+            a_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
+        }
+#pragma unroll
+        for (int i = 0; i < B_COPIES; ++i) {
+            int row = (i * NW + wave) * 8 + sub_row;
+            row = row < b_rows ? row : b_rows - 1;
+            b_off[i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
+        }
+        const uint32_t lds0 = lds_address(lds);
+
+        auto issue = [&](int step, int stage) {
+            const char* ga = a_tile + static_cast<int64_t>(step) * lane::kRowBytes;
+            const char* gb = b_tile + static_cast<int64_t>(step) * lane::kRowBytes;
+            const uint32_t la = lds0 + stage * STAGE_BYTES + wave * 1024;
+#pragma unroll
+            for (int i = 0; i < A_COPIES; ++i) copy_async_16(ga, a_off[i], la + i * NW * 1024);
+#pragma unroll
+            for (int i = 0; i < B_COPIES; ++i) copy_async_16(gb, b_off[i], la + A_BYTES + i * NW * 1024);
+        };
+
+        const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+        const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
+        frag_t fa[2][MT], fb[2][NT];
+        auto read_frags = [&](int buf, int stage, int ksub) {
+            const char* st = lds + stage * STAGE_BYTES;
+            wave::load_fragments<T, MT>(fa[buf], st, a_row0, ksub, lane);
+            wave::load_fragments<T, NT>(fb[buf], st + A_BYTES, b_row0, ksub, lane);
+        };
+
+        // -- prologue: fill the slots, wait for step 0
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s)
+            if (s < ksteps) issue(s, s);
+        if (ksteps >= STAGES) wait_counts<(STAGES - 1) * COPIES, 0>();
+        else wait_counts<0, 0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        read_frags(0, 0, 0);
+
+        int stage = 0;
+        for (int t = 0; t < ksteps; ++t) {
+            const int next = stage + 1 == STAGES ? 0 : stage + 1;
+#pragma unroll
+            for (int ks = 0; ks < KSUB; ++ks) {
+                if (ks + 1 < KSUB) {
+                    read_frags((ks + 1) & 1, stage, ks + 1);
+                } else if (t + 1 < ksteps) {
+                    // Hand-over: my copies for step t+1 have landed and my reads of this
+                    // slot are done; after the barrier that holds for every wave.
+                    if (t + STAGES < ksteps) wait_counts<(STAGES - 2) * COPIES, 0>();
+                    else wait_counts<0, 0>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");  // keep the reads below on this side of the barrier
+                    if (t + STAGES < ksteps) issue(t + STAGES, stage);
+                    read_frags(0, next, 0);
+                }
+                acc.mma(fa[ks & 1], fb[ks & 1]);
+            }
+            stage = next;
+        }
+    }
+};
+
+// ------------------------------------------------------------------------------------
+// Staged main loop: any element strides and alignments; operands pass through
+// registers, are zero-filled outside the matrix and written to one LDS slot.
+// ------------------------------------------------------------------------------------
+template <typename T>
+struct Staged {
+    static constexpr int BM = 128, BN = 128, NW = 4, THREADS = 256;
+    static constexpr int WTM = 64, WTN = 64, MT = 2, NT = 2;
+    static constexpr int KSUB = lane::kTileK / 16;
+    static constexpr int A_BYTES = BM * lane::kRowBytes, B_BYTES = BN * lane::kRowBytes;
+    static constexpr int DRAIN_BYTES = NW * drain_patch_bytes(NT);
+    static constexpr int LDS_BYTES = A_BYTES + B_BYTES > DRAIN_BYTES ? A_BYTES + B_BYTES : DRAIN_BYTES;
+    static constexpr int CHUNKS = BM * lane::kChunksPerRow / THREADS;  // per thread per operand
+
+    using tile_t = wave::Tile<T, MT, NT>;
+    using frag_t = typename Frag<T>::type;
+
+    // One thread's share of a 128 x 64 operand tile as CHUNKS 16-byte chunks.
+    // base: element (row 0 of the tile, k 0 of the matrix); s_row / s_k: element
+    // strides; rows: rows that exist; k0: first k of this step; k_end: end of
+    // the slice.  vec: rows are K-contiguous and every chunk is 16-byte aligned.
+    __device__ __forceinline__ static void gather(u32x4 (&regs)[CHUNKS], const char* base, int64_t s_row, int64_t s_k,
+                                  int rows, int k0, int k_end, bool vec, int tid)
+    {
+        const bool k_fast = s_k == 1;
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int q = tid + THREADS * i;
+            const int row = k_fast ? q / lane::kChunksPerRow : q % BM;
+            const int c = k_fast ? q % lane::kChunksPerRow : q / BM;
+            const int k = k0 + 8 * c;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (row < rows && k < k_end) {
+                const char* src = base + 2 * (row * s_row + k * s_k);
+                if (vec && k + 8 <= k_end) {
+                    v = *reinterpret_cast<const u32x4*>(src);
+                } else {
+                    uint32_t h[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        h[e] = (k + e < k_end) ? *reinterpret_cast<const uint16_t*>(src + 2 * e * s_k) : 0u;
+                    v = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                }
+            }
+            regs[i] = v;
+        }
+    }
+
+    __device__ __forceinline__ static void commit(const u32x4 (&regs)[CHUNKS], char* tile, bool k_fast, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int q = tid + THREADS * i;
+            const int row = k_fast ? q / lane::kChunksPerRow : q % BM;
+            const int c = k_fast ? q % lane::kChunksPerRow : q / BM;
+            *reinterpret_cast<u32x4*>(tile + lane::tile_offset(row, c)) = regs[i];
+        }
+    }
+
+    __device__ __forceinline__ static void run(tile_t& acc, const char* a_tile, int64_t a_sm, int64_t a_sk, int a_rows, bool a_vec,
+                               const char* b_tile, int64_t b_sn, int64_t b_sk, int b_rows, bool b_vec,
+                               int k_begin, int k_end, char* lds, int wave, int lane)
+    {
+        const int tid = wave * 64 + lane;
+        const int wave_m = wave >> 1, wave_n = wave & 1;
+        u32x4 ra[CHUNKS], rb[CHUNKS];
+        for (int k0 = k_begin; k0 < k_end; k0 += lane::kTileK) {
+            gather(ra, a_tile, a_sm, a_sk, a_rows, k0, k_end, a_vec, tid);
+            gather(rb, b_tile, b_sn, b_sk, b_rows, k0, k_end, b_vec, tid);
+            __syncthreads();  // the previous step's fragment reads are finished
+            commit(ra, lds, a_sk == 1, tid);
+            commit(rb, lds + A_BYTES, b_sk == 1, tid);
+            __syncthreads();
+#pragma unroll
+            for (int ks = 0; ks < KSUB; ++ks) {
+                frag_t fa[MT], fb[NT];
+                wave::load_fragments<T, MT>(fa, lds, wave_m * WTM, ks, lane);
+                wave::load_fragments<T, NT>(fb, lds + A_BYTES, wave_n * WTN, ks, lane);
+                acc.mma(fa, fb);
+            }
+        }
+    }
+};
+
+}  // namespace wg
+}  // namespace prism

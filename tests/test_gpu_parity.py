@@ -1,0 +1,329 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Acceptance (per entry, on the fp32 value before any narrowing of the output):
+    |C_gpu - ref| <= 4*K*2^-24 * sum_k|a_ik b_kj| + 1e-6
+and bit-exact results for integer-valued inputs.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_11939_amd as P
+from oracle import gemm_ref, decode_output, check_against_oracle, decode_bits
+from workloads import CONFIGS, GemmWorkload, make_inputs, to_bf16_bits, to_f16_bits
+
+from gpu_harness import (run_workload, assert_matches_oracle, tile_probe_rows, to_dev, alloc_c,
+                         c_to_numpy, workspace_for)
+
+pytestmark = pytest.mark.gpu
+
+ENC = {"bf16": to_bf16_bits, "f16": to_f16_bits}
+
+
+def _exact_int_product(w, inputs, batch_index=0):
+    """Integer-valued inputs: the exact product via float64 BLAS (every partial sum is an
+    integer far below 2^53, so the library result is exact)."""
+    a = decode_bits(inputs["A"][batch_index], w.ab_dtype)
+    b = decode_bits(inputs["B"][batch_index], w.ab_dtype)
+    a = a if w.layout_a == "row" else a.T
+    b = b if w.layout_b == "row" else b.T
+    return a @ b
+
+
+def _round_like_output(x64, c_dtype):
+    t = torch.from_numpy(np.ascontiguousarray(x64, dtype=np.float32))
+    if c_dtype == "bf16":
+        return t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    if c_dtype == "f16":
+        return t.to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+# ---- config 1: 256^3, both operands row-major, fp32 out, plus the closed-form variants ----------
+
+def test_cfg1_random_every_entry():
+    w = CONFIGS["cfg1_256_rowrow_f32"]
+    inp = make_inputs(w)
+    c, plan = run_workload(w, inp)
+    assert plan["kernel"] == 1            # row-major B goes through the staged kernel
+    assert_matches_oracle(w, inp, c)
+
+
+def test_cfg1_identity_ones_rank1_exact():
+    w = CONFIGS["cfg1_256_rowrow_f32"]
+    inp = make_inputs(w)
+    n = w.N
+    # identity B: exact copy of A
+    eye = to_bf16_bits(np.eye(n, dtype=np.float32).ravel()).reshape(1, n, n)
+    c, _ = run_workload(w, {"A": inp["A"], "B": eye, "bias": None})
+    assert (c[0].astype(np.float64) == decode_bits(inp["A"][0], "bf16")).all()
+    # all ones: K everywhere
+    ones = to_bf16_bits(np.ones(n * n, dtype=np.float32)).reshape(1, n, n)
+    c, _ = run_workload(w, {"A": ones, "B": ones, "bias": None})
+    assert (c[0] == float(w.K)).all()
+    # rank one: A = u v^T with small integers, B = ones  ->  u_i * sum(v)
+    rng = np.random.default_rng(3)
+    u = rng.integers(-4, 5, size=(n, 1)).astype(np.float32)
+    v = rng.integers(-4, 5, size=(1, n)).astype(np.float32)
+    a = to_bf16_bits((u @ v).ravel()).reshape(1, n, n)
+    c, _ = run_workload(w, {"A": a, "B": ones, "bias": None})
+    assert (c[0] == (u * v.sum())).all()
+
+
+# ---- config 2: 4096^3 bf16 -> bf16, the launch the benchmark times --------------------------
+
+def test_cfg2_sampled_rows_and_f32_cross_check():
+    w = CONFIGS["cfg2_4096_bf16"]
+    inp = make_inputs(w)
+    c, plan = run_workload(w, inp)
+    assert plan["kernel"] == 2 and plan["split_k"] == 1
+    rows = tile_probe_rows(w.M, plan["tile_m"])
+    assert_matches_oracle(w, inp, c, rows=rows, what="bf16 out")
+    # same launch with an fp32 result: strict bound, and the bf16 result is its rounding
+    c32, _ = run_workload(w, inp, c_dtype="f32")
+    assert_matches_oracle(w, inp, c32, c_dtype="f32", rows=rows, what="f32 out")
+    assert (_round_like_output(c32[0], "bf16") == c[0]).all()
+    # run-to-run determinism
+    c_again, _ = run_workload(w, inp)
+    assert (c_again == c).all()
+
+
+def test_cfg2_integers_bit_exact_every_entry():
+    w = CONFIGS["cfg2_4096_bf16"].with_(dist_a=("ints", -8, 8), dist_b=("ints", -8, 8))
+    inp = make_inputs(w)
+    c, _ = run_workload(w, inp)
+    want = _round_like_output(_exact_int_product(w, inp), "bf16")
+    assert (c[0] == want).all()
+
+
+# ---- config 3: projection shape with fused bias -----------------------------------------------
+
+def test_cfg3_bias_sampled_rows():
+    w = CONFIGS["cfg3_proj_bias"]
+    inp = make_inputs(w)
+    c, plan = run_workload(w, inp)
+    assert plan["kernel"] == 2
+    rows = tile_probe_rows(w.M, plan["tile_m"], per_tile=(0, 77, 128, 255))
+    assert_matches_oracle(w, inp, c, rows=rows)
+
+
+def test_cfg3_integers_bit_exact_sampled_rows():
+    w = CONFIGS["cfg3_proj_bias"].with_(dist_a=("ints", -8, 8), dist_b=("ints", -8, 8))
+    inp = make_inputs(w)
+    inp["bias"] = np.round(inp["bias"] * 4).astype(np.float32)     # integer bias
+    c, _ = run_workload(w, inp)
+    rows = np.array(tile_probe_rows(w.M, 256, per_tile=(5, 250)))
+    a = decode_bits(inp["A"][0][rows], "bf16")
+    b = decode_bits(inp["B"][0], "bf16").T
+    want = _round_like_output(a @ b + inp["bias"].astype(np.float64)[None, :], "bf16")
+    assert (c[0][rows] == want).all()
+
+
+# ---- config 4: fp16, K = 32768, split-K reduced on the device -------------------------------------
+
+def test_cfg4_splitk_sampled_rows_and_determinism():
+    w = CONFIGS["cfg4_splitk_f16"]
+    inp = make_inputs(w)
+    c, plan = run_workload(w, inp)
+    assert plan["split_k"] > 1
+    rows = tile_probe_rows(w.M, plan["tile_m"], per_tile=(0, 33, 130, 255))
+    assert_matches_oracle(w, inp, c, rows=rows)
+    c2, _ = run_workload(w, inp)
+    assert (c2 == c).all()                                         # fixed reduction order
+
+
+def test_cfg4_integers_bit_exact_every_entry():
+    w = CONFIGS["cfg4_splitk_f16"].with_(dist_a=("ints", -8, 8), dist_b=("ints", -8, 8))
+    inp = make_inputs(w)
+    c, _ = run_workload(w, inp)
+    assert (c[0].astype(np.float64) == _exact_int_product(w, inp)).all()
+
+
+# ---- config 5: 256 independent 512^3 problems ------------------------------------------------------
+
+def test_cfg5_batched_selected_problems_every_entry():
+    w = CONFIGS["cfg5_batched_512"]
+    inp = make_inputs(w)
+    c, plan = run_workload(w, inp)
+    assert plan["workgroups"] == plan["tiles_m"] * plan["tiles_n"] * w.batch
+    for b in (0, 1, 100, 255):
+        assert_matches_oracle(w, inp, c, batch_index=b, what=f"problem {b}")
+
+
+def test_cfg5_integers_bit_exact_all_problems():
+    w = CONFIGS["cfg5_batched_512"].with_(dist_a=("ints", -8, 8), dist_b=("ints", -8, 8))
+    inp = make_inputs(w)
+    c, _ = run_workload(w, inp)
+    a = decode_bits(inp["A"], "bf16")
+    b = np.swapaxes(decode_bits(inp["B"], "bf16"), 1, 2)
+    want = _round_like_output(np.matmul(a, b), "bf16")
+    assert (c == want).all()
+
+
+# ---- shapes, layouts, epilogue options, edge cases ---------------------------------------------------
+
+def _general_case(M, N, K, *, ab="bf16", cd="f32", la="row", lb="col", lc="row", pad=(0, 0, 0),
+                  alpha=1.0, beta=0.0, bias=False, split_k=0, batch=1, offset=0, seed=1, ints=False):
+    """One problem with arbitrary leading-dimension padding and pointer offset (in elements),
+    checked entry by entry against the oracle."""
+    rng = np.random.default_rng(seed)
+
+    def draw(*shape):
+        if ints:
+            return rng.integers(-8, 9, size=shape).astype(np.float32)
+        return rng.standard_normal(shape).astype(np.float32)
+
+    a_log = draw(batch, M, K)
+    b_log = draw(batch, K, N)
+    c_log = draw(batch, M, N)
+    bias_v = draw(N) if bias else None
+    lda = (K if la == "row" else M) + pad[0]
+    ldb = (N if lb == "row" else K) + pad[1]
+    ldc = (N if lc == "row" else M) + pad[2]
+
+    def store(x, rows, cols, layout, ld, enc):
+        """x [batch, rows, cols] logical -> flat padded storage per problem."""
+        outer, inner = (rows, cols) if layout == "row" else (cols, rows)
+        buf = np.zeros((batch, max(outer, 1), max(ld, 1)), dtype=np.float32) + 7.0
+        src = x if layout == "row" else np.swapaxes(x, 1, 2)
+        buf[:, :outer, :inner] = src
+        return enc(buf.ravel()).reshape(batch, -1)
+
+    A = store(a_log, M, K, la, lda, ENC[ab])
+    B = store(b_log, K, N, lb, ldb, ENC[ab])
+    c_enc = (lambda v: v.astype(np.float32)) if cd == "f32" else ENC[cd]
+    C0 = store(c_log, M, N, lc, ldc, c_enc)
+    strideA, strideB, strideC = A.shape[1], B.shape[1], C0.shape[1]
+
+    def dev(flat, dtype16=True):
+        """copy with `offset` leading elements so the base pointer can be misaligned"""
+        flat = np.ascontiguousarray(flat).ravel()
+        t = torch.empty(flat.size + offset, dtype=torch.int16 if dtype16 else torch.float32, device="cuda")
+        src = torch.from_numpy(flat.view(np.int16) if dtype16 else flat).cuda()
+        t[offset:] = src
+        return t
+
+    dA, dB = dev(A), dev(B)
+    dC = dev(C0, dtype16=(cd != "f32"))
+    dbias = None if bias_v is None else torch.from_numpy(bias_v).cuda()
+    desc = P.make_desc(ab_dtype=ab, c_dtype=cd, layout_a=la, layout_b=lb, layout_c=lc,
+                       alpha=alpha, beta=beta, bias=dbias, split_k=split_k)
+    ws = workspace_for(desc, M, N, K, batch)
+    es_c = 4 if cd == "f32" else 2
+    P.gemm(dA.data_ptr() + 2 * offset, dB.data_ptr() + 2 * offset, dC.data_ptr() + es_c * offset,
+           M=M, N=N, K=K, desc=desc, lda=lda, ldb=ldb, ldc=ldc, batch=batch,
+           strideA=strideA, strideB=strideB, strideC=strideC)
+    torch.cuda.synchronize()
+    out = c_to_numpy(dC[offset:], cd).reshape(batch, -1)
+
+    outer, inner = (M, N) if lc == "row" else (N, M)
+    for b in range(batch):
+        got = out[b].reshape(max(outer, 1), ldc)[:outer, :inner]
+        old = C0[b].reshape(max(outer, 1), ldc)
+        # padding of C must be untouched
+        assert (out[b].reshape(max(outer, 1), ldc)[:, inner:] == old[:, inner:]).all()
+        got = got if lc == "row" else got.T
+        c_in = decode_output(old[:outer, :inner], cd)
+        c_in = c_in if lc == "row" else c_in.T
+        ref, mag = gemm_ref(A[b], B[b], ab_dtype=ab, M=M, N=N, K=K, layout_a=la, layout_b=lb,
+                            lda=lda, ldb=ldb, alpha=alpha, beta=beta, bias=bias_v,
+                            c_in=c_in if beta != 0.0 else None)
+        if M and N:
+            res = check_against_oracle(decode_output(np.ascontiguousarray(got), cd), ref, mag, K, cd)
+            assert res["ok"], (M, N, K, la, lb, lc, res)
+            if ints and cd == "f32" and alpha == 1.0 and beta == 0.0:
+                assert (decode_output(np.ascontiguousarray(got), cd) == ref).all()
+    del ws
+
+
+@pytest.mark.parametrize("la", ["row", "col"])
+@pytest.mark.parametrize("lb", ["row", "col"])
+@pytest.mark.parametrize("lc", ["row", "col"])
+def test_all_layouts_ragged(la, lb, lc):
+    _general_case(130, 71, 100, la=la, lb=lb, lc=lc, pad=(3, 5, 2), bias=True, alpha=0.5)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 1, 33), (1, 257, 64), (33, 7, 255), (255, 257, 63),
+                                   (257, 255, 65), (129, 129, 129), (64, 64, 4096)])
+def test_odd_shapes_staged_and_pipelined(M, N, K):
+    _general_case(M, N, K, ints=True)
+    _general_case(M, N, K, cd="bf16", bias=True)
+
+
+@pytest.mark.parametrize("cfg", ["0", "1", "2"])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (300, 520, 192), (512, 768, 128), (100, 90, 640)])
+def test_every_pipeline_config_with_edges(cfg, M, N, K, monkeypatch):
+    monkeypatch.setenv("PRISM_GEMM_CONFIG", cfg)
+    desc = P.make_desc(c_dtype="f32")
+    s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, 0, None, K, 0, None, N, 0, 1)
+    assert s == 0 and plan.kernel == 2
+    _general_case(M, N, K, ints=True)
+    _general_case(M, N, K, ab="f16", cd="f16", bias=True, alpha=-1.25)
+
+
+@pytest.mark.parametrize("ksteps", [1, 2, 3, 4, 5, 7])
+def test_pipeline_short_k_loops(ksteps, monkeypatch):
+    """1, 2, 3 ... K steps exercise the prologue / tail of the slot rotation."""
+    for cfg in ("0", "2"):
+        monkeypatch.setenv("PRISM_GEMM_CONFIG", cfg)
+        _general_case(256, 256, 64 * ksteps, ints=True)
+
+
+def test_unaligned_pointers_and_odd_ld():
+    _general_case(96, 80, 128, pad=(1, 1, 1), offset=1, bias=True)
+    _general_case(96, 80, 128, pad=(0, 0, 0), offset=3, cd="bf16")
+
+
+@pytest.mark.parametrize("cd", ["f32", "bf16", "f16"])
+def test_alpha_beta_bias(cd):
+    _general_case(200, 136, 192, cd=cd, alpha=1.5, beta=-0.75, bias=True)
+    _general_case(200, 136, 192, cd=cd, alpha=0.0, beta=2.0)
+
+
+@pytest.mark.parametrize("split", [2, 3, 5, 64])
+def test_forced_split_k(split):
+    _general_case(256, 256, 1024, split_k=split, ints=True)
+    _general_case(100, 60, 1000, split_k=split, lb="row", cd="bf16", bias=True, beta=0.5)
+
+
+def test_batched_with_padding_and_split():
+    _general_case(120, 72, 256, batch=5, pad=(8, 8, 4), bias=True)
+    _general_case(128, 128, 512, batch=3, split_k=4, ints=True)
+
+
+def test_degenerate_sizes():
+    _general_case(5, 9, 0, bias=True)                  # K == 0: C <- bias
+    _general_case(5, 9, 0, beta=2.0, cd="bf16")        # K == 0: C <- beta*C
+    _general_case(0, 9, 4)
+    _general_case(5, 0, 4)
+
+
+def test_subnormal_inputs_report_only(capsys):
+    """fp16 subnormal operands: the contribution of a flushed term is far inside the bound;
+    this only reports what the hardware did."""
+    M = N = 32
+    K = 64
+    a = np.full((M, K), 0x0001, dtype=np.uint16)       # 2^-24
+    b = np.full((N, K), 0x3C00, dtype=np.uint16)       # 1.0
+    dA, dB = to_dev(a), to_dev(b)
+    dC = alloc_c(M * N, "f32")
+    desc = P.make_desc(ab_dtype="f16", c_dtype="f32")
+    P.gemm(dA, dB, dC, M=M, N=N, K=K, desc=desc)
+    torch.cuda.synchronize()
+    got = float(dC[0].item())
+    ref, mag = gemm_ref(a, b, ab_dtype="f16", M=M, N=N, K=K)
+    print(f"subnormal fp16 operands: gpu={got!r} exact={ref[0, 0]!r}")
+    assert abs(got - ref[0, 0]) <= 4 * K * 2.0 ** -24 * mag[0, 0] + 1e-6
+
+
+def test_error_codes_do_not_launch():
+    d = P.make_desc()
+    x = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
+    y = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
+    z = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
+    assert P.prism_gemm(d, 64, 64, 64, x, 63, y, 64, z, 64) == P.Status.INVALID_ARG
+    assert P.prism_gemm(d, 64, 64, 64, x, 64, y, 64, x, 64) == P.Status.INVALID_ARG   # C aliases A
+    d2 = P.make_desc(split_k=4)
+    assert P.prism_gemm(d2, 64, 64, 512, x, 512, y, 512, z, 64) == P.Status.WORKSPACE
