@@ -179,9 +179,9 @@ def _general_case(M, N, K, *, ab="bf16", cd="f32", la="row", lb="col", lc="row",
     b_log = draw(batch, K, N)
     c_log = draw(batch, M, N)
     bias_v = draw(N) if bias else None
-    lda = (K if la == "row" else M) + pad[0]
-    ldb = (N if lb == "row" else K) + pad[1]
-    ldc = (N if lc == "row" else M) + pad[2]
+    lda = max((K if la == "row" else M) + pad[0], 1)
+    ldb = max((N if lb == "row" else K) + pad[1], 1)
+    ldc = max((N if lc == "row" else M) + pad[2], 1)
 
     def store(x, rows, cols, layout, ld, enc):
         """x [batch, rows, cols] logical -> flat padded storage per problem."""
@@ -320,8 +320,8 @@ def test_subnormal_inputs_report_only(capsys):
 
 def test_error_codes_do_not_launch():
     d = P.make_desc()
-    x = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
-    y = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
+    x = torch.zeros(64 * 512, dtype=torch.int16, device="cuda")
+    y = torch.zeros(64 * 512, dtype=torch.int16, device="cuda")
     z = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
     assert P.prism_gemm(d, 64, 64, 64, x, 63, y, 64, z, 64) == P.Status.INVALID_ARG
     assert P.prism_gemm(d, 64, 64, 64, x, 64, y, 64, x, 64) == P.Status.INVALID_ARG   # C aliases A
