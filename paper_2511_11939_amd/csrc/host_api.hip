@@ -190,7 +190,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     p.tiles_m = static_cast<int>(tiles_m);
     p.tiles_n = static_cast<int>(tiles_n);
 
-    plan.tile_m = tile_m; plan.tile_n = tile_n; plan.tile_k = 64; plan.waves = waves;
+    plan.tile_m = tile_m; plan.tile_n = tile_n; plan.waves = waves;
+    plan.tile_k = plan.kernel == 2 ? prism::kPipeConfigs[out->pipe_config].tile_k : 64;
     plan.split_k = static_cast<int32_t>(split);
     plan.tiles_m = tiles_m; plan.tiles_n = tiles_n;
     plan.workgroups = units * split;

@@ -12,9 +12,9 @@
 namespace prism {
 
 const PipeConfig kPipeConfigs[kNumPipeConfigs] = {
-    {0, 256, 256, 4, 2, "256x256x64_w4_s2"},
-    {1, 256, 256, 8, 2, "256x256x64_w8_s2"},
-    {2, 128, 128, 4, 3, "128x128x64_w4_s3"},
+    {0, 256, 256, 64, 4, 2, "256x256x64_w4_s2"},
+    {1, 256, 256, 64, 8, 2, "256x256x64_w8_s2"},
+    {2, 128, 128, 64, 4, 3, "128x128x64_w4_s3"},
 };
 
 namespace {
@@ -67,10 +67,10 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
         });
 }
 
-template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_pipelined(const GemmParams p)
 {
-    using P = wg::Pipeline<T, BM, BN, WAVES_M, WAVES_N, STAGES>;
+    using P = wg::Pipeline<T, BM, BN, BK, WAVES_M, WAVES_N, STAGES>;
     __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_pipelined(const Ge
     typename P::tile_t acc;
     acc.clear();
     P::run(acc, a_tile, static_cast<uint32_t>(2 * p.a_sm), a_rows, b_tile, static_cast<uint32_t>(2 * p.b_sn),
-           b_rows, (q.k_end - q.k_begin) / lane::kTileK, lds, wave, lane);
+           b_rows, (q.k_end - q.k_begin) / BK, lds, wave, lane);
 
     epilogue<typename P::tile_t, P::MT, P::NT>(p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
                                                q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane);
@@ -146,10 +146,10 @@ __global__ __launch_bounds__(256) void splitk_reduce(const GemmParams p)
     }
 }
 
-template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
 hipError_t launch_pipe(const GemmParams& p, int workgroups, hipStream_t stream)
 {
-    hipLaunchKernelGGL((gemm_pipelined<T, BM, BN, WAVES_M, WAVES_N, STAGES>), dim3(workgroups),
+    hipLaunchKernelGGL((gemm_pipelined<T, BM, BN, BK, WAVES_M, WAVES_N, STAGES>), dim3(workgroups),
                        dim3(WAVES_M * WAVES_N * 64), 0, stream, p);
     return hipGetLastError();
 }
@@ -158,9 +158,9 @@ template <typename T>
 hipError_t launch_pipe_config(int config, const GemmParams& p, int workgroups, hipStream_t stream)
 {
     switch (config) {
-    case 0: return launch_pipe<T, 256, 256, 2, 2, 2>(p, workgroups, stream);
-    case 1: return launch_pipe<T, 256, 256, 2, 4, 2>(p, workgroups, stream);
-    case 2: return launch_pipe<T, 128, 128, 2, 2, 3>(p, workgroups, stream);
+    case 0: return launch_pipe<T, 256, 256, 64, 2, 2, 2>(p, workgroups, stream);
+    case 1: return launch_pipe<T, 256, 256, 64, 2, 4, 2>(p, workgroups, stream);
+    case 2: return launch_pipe<T, 128, 128, 64, 2, 2, 3>(p, workgroups, stream);
     default: return hipErrorInvalidValue;
     }
 }

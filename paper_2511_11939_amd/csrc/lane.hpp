@@ -30,33 +30,39 @@ template <> struct Frag<f16_t> { using type = f16x8; };
 namespace lane {
 
 // ---- LDS tile layout ---------------------------------------------------------
-// An operand tile in LDS is `rows` x 64 elements, K contiguous: 128 bytes per
-// row, i.e. eight 16-byte chunks.  Chunk c of row r is kept at chunk position
-// c ^ swizzle(r).  With the swizzle below, 16 lanes that read the same logical
-// chunk of 16 consecutive rows touch 16 distinct 16-byte bank groups of a
-// 256-byte LDS row, and 8 consecutive rows touch 8 distinct groups of a
-// 128-byte row, so the 128-bit fragment reads are conflict free.
-constexpr int kTileK = 64;          // elements per tile row
-constexpr int kRowBytes = kTileK * 2;
+// An operand tile in LDS is `rows` x BK elements, K contiguous, made of
+// 16-byte chunks (8 elements).  Chunk c of row r is kept at chunk position
+// c ^ swizzle(r).  The swizzles are chosen so that 16 lanes reading the same
+// logical chunk of 16 consecutive rows touch 16 distinct 16-byte bank groups
+// of a 256-byte LDS row (and 8 consecutive rows 8 distinct groups of a
+// 128-byte row): the 128-bit fragment reads are then free of bank conflicts.
 constexpr int kChunkBytes = 16;
-constexpr int kChunksPerRow = kRowBytes / kChunkBytes;
 
-__host__ __device__ constexpr int swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
-
-__host__ __device__ constexpr int tile_offset(int row, int chunk)
-{
-    return row * kRowBytes + ((chunk ^ swizzle(row)) * kChunkBytes);
-}
+template <int BK>
+struct TileLayout {
+    static_assert(BK == 32 || BK == 64, "tile rows are 64 or 128 bytes");
+    static constexpr int kTileK = BK;
+    static constexpr int kRowBytes = BK * 2;
+    static constexpr int kChunksPerRow = kRowBytes / kChunkBytes;
+    __host__ __device__ static constexpr int swizzle(int row)
+    {
+        return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (((row >> 1) ^ (row >> 2)) & 3);
+    }
+    __host__ __device__ static constexpr int offset(int row, int chunk)
+    {
+        return row * kRowBytes + ((chunk ^ swizzle(row)) * kChunkBytes);
+    }
+};
 
 // One lane's share of a 32-row x 16-k MFMA operand fragment: 8 consecutive k
 // of row (row0 + lane%32), taken from k-chunk (2*ksub + lane/32) of the tile.
-template <typename T>
+template <typename T, int BK>
 __device__ __forceinline__ typename Frag<T>::type
 load_fragment(const char* tile, int row0, int ksub, int lane)
 {
     const int row = row0 + (lane & 31);
     const int chunk = 2 * ksub + (lane >> 5);
-    const u32x4 raw = *reinterpret_cast<const u32x4*>(tile + tile_offset(row, chunk));
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(tile + TileLayout<BK>::offset(row, chunk));
     return __builtin_bit_cast(typename Frag<T>::type, raw);
 }
 

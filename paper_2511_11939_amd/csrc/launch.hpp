@@ -10,7 +10,7 @@ namespace prism {
 // Workgroup-tile configurations of the direct-to-LDS pipeline.
 struct PipeConfig {
     int id;
-    int tile_m, tile_n, waves, stages;
+    int tile_m, tile_n, tile_k, waves, stages;
     const char* name;
 };
 constexpr int kNumPipeConfigs = 3;

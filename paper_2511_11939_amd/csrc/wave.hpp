@@ -54,12 +54,12 @@ struct Tile {
 
 // Fragments of one k sub-step for a wave tile whose first row in the LDS tile
 // is row0: MT (or NT) blocks of 32 rows.
-template <typename T, int NBLK>
+template <typename T, int BK, int NBLK>
 __device__ __forceinline__ void load_fragments(typename Frag<T>::type (&f)[NBLK], const char* tile,
                                                int row0, int ksub, int lane)
 {
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) f[i] = lane::load_fragment<T>(tile, row0 + 32 * i, ksub, lane);
+    for (int i = 0; i < NBLK; ++i) f[i] = lane::load_fragment<T, BK>(tile, row0 + 32 * i, ksub, lane);
 }
 
 }  // namespace wave

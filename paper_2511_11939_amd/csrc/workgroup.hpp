@@ -12,6 +12,8 @@
 // would insert it (section 5, synchronisation at loop back-edges).
 #pragma once
 
+#include <type_traits>
+
 #include "lane.hpp"
 #include "wave.hpp"
 
@@ -101,20 +103,22 @@ __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, S
 // ------------------------------------------------------------------------------------
 // Pipelined main loop: K-contiguous operands, direct-to-LDS copies, STAGES slots.
 // ------------------------------------------------------------------------------------
-template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
 struct Pipeline {
+    using L = lane::TileLayout<BK>;
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     static constexpr int MT = WTM / 32, NT = WTN / 32;
-    static constexpr int KSUB = lane::kTileK / 16;
-    static constexpr int A_BYTES = BM * lane::kRowBytes, B_BYTES = BN * lane::kRowBytes;
+    static constexpr int KSUB = BK / 16;
+    static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static constexpr int A_COPIES = BM / 8 / NW, B_COPIES = BN / 8 / NW;  // per wave per K step
+    static constexpr int COPY_ROWS = 1024 / L::kRowBytes;  // rows moved by one wave-wide copy
+    static constexpr int A_COPIES = BM / COPY_ROWS / NW, B_COPIES = BN / COPY_ROWS / NW;  // per wave per K step
     static constexpr int COPIES = A_COPIES + B_COPIES;
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
-    static_assert(NW % 2 == 0, "row-block parity must be a per-wave constant");
+    static_assert(BM % (COPY_ROWS * NW) == 0 && BN % (COPY_ROWS * NW) == 0, "tile rows must split over the waves");
+    static_assert((NW * COPY_ROWS) % 16 == 0, "the swizzle of a lane's row must not depend on the copy index");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
     static_assert(LDS_BYTES <= 163840, "LDS budget of one gfx950 compute unit");
     static_assert(NW * drain_patch_bytes(NT) <= LDS_BYTES, "epilogue patches reuse the operand slots");
@@ -126,80 +130,142 @@ struct Pipeline {
     // a_tile / b_tile: uniform byte pointers to element (first row of the tile,
     // first k of the slice); a_ld / b_ld: row pitch in bytes; a_rows / b_rows:
     // rows of the tile that exist (>= 1; missing rows re-read the last one and
-    // their results are never stored).  ksteps >= 1 steps of 64 k each.
+    // their results are never stored).  ksteps >= 1 steps of BK k each.
+    //
+    // Schedule of one K step (KSUB sub-steps of 16 k, NM = MT*NT MFMAs each):
+    //   sub-steps 0 .. KSUB-2 : MFMAs of sub-step s, the fragment reads of
+    //                           sub-step s+1 dealt one by one between them;
+    //   sub-step KSUB-1       : wait for my copies of the next step, barrier,
+    //                           then the MFMAs with the copies of step
+    //                           t+STAGES (into the slot just retired) and the
+    //                           fragment reads of (t+1, 0) dealt between them.
+    // Every piece is pinned with a scheduling fence so the matrix pipe always
+    // has the next MFMA queued while the memory instructions issue.
     __device__ __forceinline__ static void run(tile_t& acc, const char* a_tile, uint32_t a_ld, int a_rows,
                                const char* b_tile, uint32_t b_ld, int b_rows, int ksteps,
                                char* lds, int wave, int lane)
     {
-        // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave), 8 rows x 8 chunks;
-        //    lane l fills chunk position l%8 of row l/8 with the logical chunk the swizzle wants.
-        const int sub_row = lane >> 3;
-        const int chunk = (lane & 7) ^ lane::swizzle(8 * (wave & 1) + sub_row);
-        uint32_t a_off[A_COPIES], b_off[B_COPIES];
+        constexpr int NM = MT * NT;   // MFMAs per sub-step
+        constexpr int NR = MT + NT;   // fragment reads per sub-step
+        // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave) of COPY_ROWS rows;
+        //    a lane fills one chunk position of one row with the logical chunk the swizzle wants.
+        const int sub_row = lane / L::kChunksPerRow;
+        const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
+        uint32_t g_off[COPIES];
 #pragma unroll
         for (int i = 0; i < A_COPIES; ++i) {
-            int row = (i * NW + wave) * 8 + sub_row;
+            int row = (i * NW + wave) * COPY_ROWS + sub_row;
             row = row < a_rows ? row : a_rows - 1;
-            a_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
+            g_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
         }
 #pragma unroll
         for (int i = 0; i < B_COPIES; ++i) {
-            int row = (i * NW + wave) * 8 + sub_row;
+            int row = (i * NW + wave) * COPY_ROWS + sub_row;
             row = row < b_rows ? row : b_rows - 1;
-            b_off[i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
+            g_off[A_COPIES + i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
         }
-        const uint32_t lds0 = lds_address(lds);
+        const uint32_t lds0 = lds_address(lds) + wave * 1024;
 
-        auto issue = [&](int step, int stage) {
-            const char* ga = a_tile + static_cast<int64_t>(step) * lane::kRowBytes;
-            const char* gb = b_tile + static_cast<int64_t>(step) * lane::kRowBytes;
-            const uint32_t la = lds0 + stage * STAGE_BYTES + wave * 1024;
-#pragma unroll
-            for (int i = 0; i < A_COPIES; ++i) copy_async_16(ga, a_off[i], la + i * NW * 1024);
-#pragma unroll
-            for (int i = 0; i < B_COPIES; ++i) copy_async_16(gb, b_off[i], la + A_BYTES + i * NW * 1024);
+        // copy number c (0 .. COPIES-1) of K step `step` into slot `stage`
+        auto copy = [&](int c, int step, int stage) {
+            const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
+            const uint32_t slot = lds0 + stage * STAGE_BYTES;
+            if (c < A_COPIES) copy_async_16(a_tile + k_bytes, g_off[c], slot + c * NW * 1024);
+            else copy_async_16(b_tile + k_bytes, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
         };
 
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
         frag_t fa[2][MT], fb[2][NT];
-        auto read_frags = [&](int buf, int stage, int ksub) {
+        // read number r (0 .. NR-1) of sub-step ksub of slot `stage` into buffer `buf`;
+        // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
+        auto read = [&](int r, int buf, int stage, int ksub) {
             const char* st = lds + stage * STAGE_BYTES;
-            wave::load_fragments<T, MT>(fa[buf], st, a_row0, ksub, lane);
-            wave::load_fragments<T, NT>(fb[buf], st + A_BYTES, b_row0, ksub, lane);
+            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(st, a_row0, ksub, lane);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(st + A_BYTES, b_row0 + 32 * (r - 1), ksub, lane);
+            else fa[buf][r - NT] = lane::load_fragment<T, BK>(st, a_row0 + 32 * (r - NT), ksub, lane);
+        };
+        auto mfma = [&](int m, int buf) {
+            const int i = m / NT, j = m % NT;
+            acc.acc[i][j] = wave::mfma_32x32x16(fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
 
-        // -- prologue: fill the slots, wait for step 0
+        // -- prologue: fill the slots, wait for step 0, fetch its first fragments
 #pragma unroll
         for (int s = 0; s < STAGES; ++s)
-            if (s < ksteps) issue(s, s);
+            if (s < ksteps) {
+#pragma unroll
+                for (int c = 0; c < COPIES; ++c) copy(c, s, s);
+            }
         if (ksteps >= STAGES) wait_counts<(STAGES - 1) * COPIES, 0>();
         else wait_counts<0, 0>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        read_frags(0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
 
-        int stage = 0;
-        for (int t = 0; t < ksteps; ++t) {
-            const int next = stage + 1 == STAGES ? 0 : stage + 1;
+        // One K step.  ISSUE: copies for step t+STAGES exist.  LAST: no step follows.
+        auto k_step = [&](auto issue_c, auto last_c, int t, int stage, int next) {
+            constexpr bool ISSUE = decltype(issue_c)::value;
+            constexpr bool LAST = decltype(last_c)::value;
 #pragma unroll
             for (int ks = 0; ks < KSUB; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
                 if (ks + 1 < KSUB) {
-                    read_frags((ks + 1) & 1, stage, ks + 1);
-                } else if (t + 1 < ksteps) {
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) {
+                        // reads are dealt over the first MFMAs of the group
+                        constexpr int per = (NR + NM - 1) / NM;
+#pragma unroll
+                        for (int r = m * per; r < (m + 1) * per && r < NR; ++r) read(r, nxt, stage, ks + 1);
+                        mfma(m, cur);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else if (!LAST) {
                     // Hand-over: my copies for step t+1 have landed and my reads of this
                     // slot are done; after the barrier that holds for every wave.
-                    if (t + STAGES < ksteps) wait_counts<(STAGES - 2) * COPIES, 0>();
+                    if (ISSUE) wait_counts<(STAGES - 2) * COPIES, 0>();
                     else wait_counts<0, 0>();
                     __builtin_amdgcn_s_barrier();
-                    asm volatile("" ::: "memory");  // keep the reads below on this side of the barrier
-                    if (t + STAGES < ksteps) issue(t + STAGES, stage);
-                    read_frags(0, next, 0);
+                    asm volatile("" ::: "memory");  // keep what follows on this side of the barrier
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) {
+                        if (ISSUE) {
+                            constexpr int per = (COPIES + NM - 1) / NM;
+#pragma unroll
+                            for (int c = m * per; c < (m + 1) * per && c < COPIES; ++c) copy(c, t + STAGES, stage);
+                        }
+                        // the fragment reads of the next step follow at once: they are what the
+                        // top of the next K step waits for
+                        constexpr int per_r = (NR + NM - 1) / NM;
+#pragma unroll
+                        for (int r = m * per_r; r < (m + 1) * per_r && r < NR; ++r) read(r, nxt, next, 0);
+                        mfma(m, cur);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) mfma(m, cur);
                 }
-                acc.mma(fa[ks & 1], fb[ks & 1]);
             }
+        };
+        static_assert(KSUB % 2 == 0, "fragment buffers must return to slot 0 at the end of a K step");
+
+        using yes = std::integral_constant<bool, true>;
+        using no = std::integral_constant<bool, false>;
+        int stage = 0, t = 0;
+        for (; t + STAGES < ksteps; ++t) {
+            const int next = stage + 1 == STAGES ? 0 : stage + 1;
+            k_step(yes{}, no{}, t, stage, next);
             stage = next;
         }
+        for (; t + 1 < ksteps; ++t) {
+            const int next = stage + 1 == STAGES ? 0 : stage + 1;
+            k_step(no{}, no{}, t, stage, next);
+            stage = next;
+        }
+        k_step(no{}, yes{}, t, stage, stage);
     }
 };
 
@@ -209,13 +275,14 @@ struct Pipeline {
 // ------------------------------------------------------------------------------------
 template <typename T>
 struct Staged {
-    static constexpr int BM = 128, BN = 128, NW = 4, THREADS = 256;
+    using L = lane::TileLayout<64>;
+    static constexpr int BM = 128, BN = 128, BK = 64, NW = 4, THREADS = 256;
     static constexpr int WTM = 64, WTN = 64, MT = 2, NT = 2;
-    static constexpr int KSUB = lane::kTileK / 16;
-    static constexpr int A_BYTES = BM * lane::kRowBytes, B_BYTES = BN * lane::kRowBytes;
+    static constexpr int KSUB = BK / 16;
+    static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes;
     static constexpr int DRAIN_BYTES = NW * drain_patch_bytes(NT);
     static constexpr int LDS_BYTES = A_BYTES + B_BYTES > DRAIN_BYTES ? A_BYTES + B_BYTES : DRAIN_BYTES;
-    static constexpr int CHUNKS = BM * lane::kChunksPerRow / THREADS;  // per thread per operand
+    static constexpr int CHUNKS = BM * L::kChunksPerRow / THREADS;  // per thread per operand
 
     using tile_t = wave::Tile<T, MT, NT>;
     using frag_t = typename Frag<T>::type;
@@ -231,8 +298,8 @@ struct Staged {
 #pragma unroll
         for (int i = 0; i < CHUNKS; ++i) {
             const int q = tid + THREADS * i;
-            const int row = k_fast ? q / lane::kChunksPerRow : q % BM;
-            const int c = k_fast ? q % lane::kChunksPerRow : q / BM;
+            const int row = k_fast ? q / L::kChunksPerRow : q % BM;
+            const int c = k_fast ? q % L::kChunksPerRow : q / BM;
             const int k = k0 + 8 * c;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (row < rows && k < k_end) {
@@ -256,9 +323,9 @@ struct Staged {
 #pragma unroll
         for (int i = 0; i < CHUNKS; ++i) {
             const int q = tid + THREADS * i;
-            const int row = k_fast ? q / lane::kChunksPerRow : q % BM;
-            const int c = k_fast ? q % lane::kChunksPerRow : q / BM;
-            *reinterpret_cast<u32x4*>(tile + lane::tile_offset(row, c)) = regs[i];
+            const int row = k_fast ? q / L::kChunksPerRow : q % BM;
+            const int c = k_fast ? q % L::kChunksPerRow : q / BM;
+            *reinterpret_cast<u32x4*>(tile + L::offset(row, c)) = regs[i];
         }
     }
 
@@ -269,7 +336,7 @@ struct Staged {
         const int tid = wave * 64 + lane;
         const int wave_m = wave >> 1, wave_n = wave & 1;
         u32x4 ra[CHUNKS], rb[CHUNKS];
-        for (int k0 = k_begin; k0 < k_end; k0 += lane::kTileK) {
+        for (int k0 = k_begin; k0 < k_end; k0 += BK) {
             gather(ra, a_tile, a_sm, a_sk, a_rows, k0, k_end, a_vec, tid);
             gather(rb, b_tile, b_sn, b_sk, b_rows, k0, k_end, b_vec, tid);
             __syncthreads();  // the previous step's fragment reads are finished
@@ -279,8 +346,8 @@ struct Staged {
 #pragma unroll
             for (int ks = 0; ks < KSUB; ++ks) {
                 frag_t fa[MT], fb[NT];
-                wave::load_fragments<T, MT>(fa, lds, wave_m * WTM, ks, lane);
-                wave::load_fragments<T, NT>(fb, lds + A_BYTES, wave_n * WTN, ks, lane);
+                wave::load_fragments<T, BK, MT>(fa, lds, wave_m * WTM, ks, lane);
+                wave::load_fragments<T, BK, NT>(fb, lds + A_BYTES, wave_n * WTN, ks, lane);
                 acc.mma(fa, fb);
             }
         }

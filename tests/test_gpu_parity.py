@@ -266,7 +266,7 @@ def test_every_pipeline_config_with_edges(cfg, M, N, K, monkeypatch):
 @pytest.mark.parametrize("ksteps", [1, 2, 3, 4, 5, 7])
 def test_pipeline_short_k_loops(ksteps, monkeypatch):
     """1, 2, 3 ... K steps exercise the prologue / tail of the slot rotation."""
-    for cfg in ("0", "2"):
+    for cfg in ("0", "1", "2"):
         monkeypatch.setenv("PRISM_GEMM_CONFIG", cfg)
         _general_case(256, 256, 64 * ksteps, ints=True)
 
