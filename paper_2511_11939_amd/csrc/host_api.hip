@@ -133,6 +133,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     p.c_vec = aligned(p.C, c_align) && p.ldc % 4 == 0 && (p.batch == 1 || p.batch_c % 4 == 0) &&
               (!p.bias || p.bias_along_m || aligned(p.bias, 4));
     p.p_vec = p.N % 4 == 0 && aligned(d->workspace, 16);
+    p.c_vec8 = aligned(p.C, 16) && p.ldc % 8 == 0 && (p.batch == 1 || p.batch_c % 8 == 0) &&
+               (!p.bias || aligned(p.bias, 16));
 
     if (K == 0) {  // C <- bias + beta*C: only the epilogue kernel runs
         plan.kernel = 0;

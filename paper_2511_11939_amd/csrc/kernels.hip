@@ -12,9 +12,9 @@
 namespace prism {
 
 const PipeConfig kPipeConfigs[kNumPipeConfigs] = {
-    {0, 256, 256, 64, 4, 2, "256x256x64_w4_s2"},
-    {1, 256, 256, 64, 8, 2, "256x256x64_w8_s2"},
-    {2, 128, 128, 64, 4, 3, "128x128x64_w4_s3"},
+    {0, 256, 256, 64, 4, 2, "256x256x64_w4"},
+    {1, 256, 256, 64, 8, 2, "256x256x64_w8"},
+    {2, 128, 128, 64, 4, 2, "128x128x64_w4"},
 };
 
 namespace {
@@ -53,24 +53,32 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
     }
     const int esize = p.c_dtype == DT_F32 ? 4 : 2;
     char* c_problem = p.C + static_cast<int64_t>(q.batch) * p.batch_c * esize;
-    if (p.c_dtype == DT_BF16)
-        wg::drain<MT, NT>(acc, patch, lane, [&](int r, int c, f32x4 v) {
-            grid::finish4<DT_BF16>(p, c_problem, m_wave + r, n_wave + c, v);
+    const bool inside = m_wave + 32 * MT <= p.M && n_wave + 32 * NT <= p.N;
+    if (inside && p.c_vec8 && p.beta == 0.0f && !(p.bias && p.bias_along_m)) {
+        // Common case: whole wave tile inside C, aligned rows, nothing to read back.
+        const int n_run = n_wave + 8 * (lane % (4 * NT));
+        float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (p.bias) {
+            const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + n_run);
+            const f32x4 b1 = *reinterpret_cast<const f32x4*>(p.bias + n_run + 4);
+            bias[0] = b0[0]; bias[1] = b0[1]; bias[2] = b0[2]; bias[3] = b0[3];
+            bias[4] = b1[0]; bias[5] = b1[1]; bias[6] = b1[2]; bias[7] = b1[3];
+        }
+        const bool plain = !p.bias && p.alpha == 1.0f;
+        const int64_t row_bytes = p.ldc * esize;
+        char* dst0 = c_problem + m_wave * row_bytes + static_cast<int64_t>(n_run) * esize;
+        wg::drain_runs<MT, NT>(acc, patch, lane, [&](int r, f32x4 lo, f32x4 hi) {
+            grid::finish_run(dst0 + r * row_bytes, p.c_dtype, p.alpha, bias, plain, lo, hi);
         });
-    else if (p.c_dtype == DT_F16)
-        wg::drain<MT, NT>(acc, patch, lane, [&](int r, int c, f32x4 v) {
-            grid::finish4<DT_F16>(p, c_problem, m_wave + r, n_wave + c, v);
-        });
-    else
-        wg::drain<MT, NT>(acc, patch, lane, [&](int r, int c, f32x4 v) {
-            grid::finish4<DT_F32>(p, c_problem, m_wave + r, n_wave + c, v);
-        });
+        return;
+    }
+    wg::drain<MT, NT>(acc, patch, lane,
+                      [&](int r, int c, f32x4 v) { grid::finish4_any(p, c_problem, m_wave + r, n_wave + c, v); });
 }
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_pipelined(const GemmParams p)
+template <typename P, int BM, int BN, int BK, int WAVES_N>
+__global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
 {
-    using P = wg::Pipeline<T, BM, BN, BK, WAVES_M, WAVES_N, STAGES>;
     __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -140,17 +148,14 @@ __global__ __launch_bounds__(256) void splitk_reduce(const GemmParams p)
         }
         const int esize = p.c_dtype == DT_F32 ? 4 : 2;
         char* c_problem = p.C + static_cast<int64_t>(b) * p.batch_c * esize;
-        if (p.c_dtype == DT_BF16) grid::finish4<DT_BF16>(p, c_problem, m, n0, sum);
-        else if (p.c_dtype == DT_F16) grid::finish4<DT_F16>(p, c_problem, m, n0, sum);
-        else grid::finish4<DT_F32>(p, c_problem, m, n0, sum);
+        grid::finish4_any(p, c_problem, m, n0, sum);
     }
 }
 
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
+template <typename P, int BM, int BN, int BK, int WAVES_N>
 hipError_t launch_pipe(const GemmParams& p, int workgroups, hipStream_t stream)
 {
-    hipLaunchKernelGGL((gemm_pipelined<T, BM, BN, BK, WAVES_M, WAVES_N, STAGES>), dim3(workgroups),
-                       dim3(WAVES_M * WAVES_N * 64), 0, stream, p);
+    hipLaunchKernelGGL((gemm_pipelined<P, BM, BN, BK, WAVES_N>), dim3(workgroups), dim3(P::THREADS), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -158,9 +163,9 @@ template <typename T>
 hipError_t launch_pipe_config(int config, const GemmParams& p, int workgroups, hipStream_t stream)
 {
     switch (config) {
-    case 0: return launch_pipe<T, 256, 256, 64, 2, 2, 2>(p, workgroups, stream);
-    case 1: return launch_pipe<T, 256, 256, 64, 2, 4, 2>(p, workgroups, stream);
-    case 2: return launch_pipe<T, 128, 128, 64, 2, 2, 3>(p, workgroups, stream);
+    case 0: return launch_pipe<wg::Pipeline<T, 256, 256, 64, 2, 2, 2>, 256, 256, 64, 2>(p, workgroups, stream);
+    case 1: return launch_pipe<wg::Pipeline<T, 256, 256, 64, 2, 4, 2>, 256, 256, 64, 4>(p, workgroups, stream);
+    case 2: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2>, 128, 128, 64, 2>(p, workgroups, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -100,6 +100,49 @@ __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, S
     }
 }
 
+// Fast drain for a wave tile that lies wholly inside C: the accumulators go to
+// the patch as they are (straight from the accumulator registers), come back as
+// runs of eight consecutive n per lane, and sink(row_in_wave_tile, v_lo, v_hi)
+// finishes and stores each run (columns 8*(lane % (4*NT)) .. +7 of the wave tile).
+// Inside a patch row the 16-byte units are stored evens first, odds second, so
+// that both the writes and the two reads of a run are spread over all banks.
+template <int MT, int NT, typename TileT, typename Sink>
+__device__ __forceinline__ void drain_runs(const TileT& acc, char* patch, int lane, Sink&& sink)
+{
+    constexpr int WTN = 32 * NT;
+    constexpr int UNITS = WTN / 4;            // 16-byte units per row
+    constexpr int PITCH = (WTN + 4) * 4;      // bytes
+    constexpr int LANES_PER_ROW = WTN / 8;
+    constexpr int ROWS_PER_ITER = 64 / LANES_PER_ROW;
+    constexpr int ITERS = kDrainRows / ROWS_PER_ITER;
+    // unit u of a row sits at position (u >> 1) + (UNITS / 2) * (u & 1)
+    const int run = lane % LANES_PER_ROW, sub = lane / LANES_PER_ROW;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        char* wr = patch + lane::acc_col(lane) * PITCH;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x16& a = acc.acc[i][j];
+                // unit 8j + 2g + lane/32 of the row; its parity is lane/32
+                const int pos = 4 * j + g;  // unit_pos without the parity term
+                *reinterpret_cast<f32x4*>(wr + 16 * pos + (lane >> 5) * (UNITS / 2) * 16) =
+                    f32x4{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
+            }
+        f32x4 lo[ITERS], hi[ITERS];
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const char* rd = patch + (it * ROWS_PER_ITER + sub) * PITCH;
+            lo[it] = *reinterpret_cast<const f32x4*>(rd + 16 * run);                 // unit 2*run   -> position run
+            hi[it] = *reinterpret_cast<const f32x4*>(rd + 16 * (run + UNITS / 2));   // unit 2*run+1 -> position run + UNITS/2
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) sink(32 * i + it * ROWS_PER_ITER + sub, lo[it], hi[it]);
+        __builtin_amdgcn_sched_barrier(0);  // one pass at a time keeps the register need small
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // Pipelined main loop: K-contiguous operands, direct-to-LDS copies, STAGES slots.
 // ------------------------------------------------------------------------------------
@@ -204,9 +247,20 @@ struct Pipeline {
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
 
-        // One K step.  ISSUE: copies for step t+STAGES exist.  LAST: no step follows.
-        auto k_step = [&](auto issue_c, auto last_c, int t, int stage, int next) {
-            constexpr bool ISSUE = decltype(issue_c)::value;
+        // MFMA slot of side instruction number n when `count` of them share the slots
+        // [first, NM) of a group (wrapping round when there are more than slots).
+        auto slot_of = [](int n, int first) constexpr { return first < NM ? first + n % (NM - first) : n % NM; };
+        constexpr int HALF = COPIES / 2;
+
+        // One K step t on slot `stage`.
+        //   HEAD: the second half of the copies of step t+1 is issued in sub-step 0
+        //   TAIL: the first half of the copies of step t+2 is issued after the hand-over
+        //   LAST: no step follows (no hand-over)
+        // Splitting the copies over two groups keeps every MFMA slot down to one memory
+        // instruction, which is what a single wave can issue in the shadow of one MFMA.
+        auto k_step = [&](auto head_c, auto tail_c, auto last_c, int t, int stage, int next) {
+            constexpr bool HEAD = decltype(head_c)::value;
+            constexpr bool TAIL = decltype(tail_c)::value;
             constexpr bool LAST = decltype(last_c)::value;
 #pragma unroll
             for (int ks = 0; ks < KSUB; ++ks) {
@@ -214,33 +268,34 @@ struct Pipeline {
                 if (ks + 1 < KSUB) {
 #pragma unroll
                     for (int m = 0; m < NM; ++m) {
-                        // reads are dealt over the first MFMAs of the group
-                        constexpr int per = (NR + NM - 1) / NM;
 #pragma unroll
-                        for (int r = m * per; r < (m + 1) * per && r < NR; ++r) read(r, nxt, stage, ks + 1);
+                        for (int r = 0; r < NR; ++r)
+                            if (slot_of(r, 0) == m) read(r, nxt, stage, ks + 1);
+                        if (HEAD && ks == 0) {
+#pragma unroll
+                            for (int c = HALF; c < COPIES; ++c)
+                                if (slot_of(c - HALF, NR) == m) copy(c, t + 1, next);
+                        }
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 } else if (!LAST) {
                     // Hand-over: my copies for step t+1 have landed and my reads of this
                     // slot are done; after the barrier that holds for every wave.
-                    if (ISSUE) wait_counts<(STAGES - 2) * COPIES, 0>();
-                    else wait_counts<0, 0>();
+                    wait_counts<0, 0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");  // keep what follows on this side of the barrier
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int m = 0; m < NM; ++m) {
-                        if (ISSUE) {
-                            constexpr int per = (COPIES + NM - 1) / NM;
 #pragma unroll
-                            for (int c = m * per; c < (m + 1) * per && c < COPIES; ++c) copy(c, t + STAGES, stage);
+                        for (int r = 0; r < NR; ++r)
+                            if (slot_of(r, 0) == m) read(r, nxt, next, 0);
+                        if (TAIL) {
+#pragma unroll
+                            for (int c = 0; c < HALF; ++c)
+                                if (slot_of(c, NR) == m) copy(c, t + 2, stage);
                         }
-                        // the fragment reads of the next step follow at once: they are what the
-                        // top of the next K step waits for
-                        constexpr int per_r = (NR + NM - 1) / NM;
-#pragma unroll
-                        for (int r = m * per_r; r < (m + 1) * per_r && r < NR; ++r) read(r, nxt, next, 0);
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -251,21 +306,25 @@ struct Pipeline {
             }
         };
         static_assert(KSUB % 2 == 0, "fragment buffers must return to slot 0 at the end of a K step");
+        static_assert(STAGES == 2 && COPIES % 2 == 0, "the copy schedule below is written for two slots");
 
         using yes = std::integral_constant<bool, true>;
         using no = std::integral_constant<bool, false>;
-        int stage = 0, t = 0;
-        for (; t + STAGES < ksteps; ++t) {
-            const int next = stage + 1 == STAGES ? 0 : stage + 1;
-            k_step(yes{}, no{}, t, stage, next);
-            stage = next;
+        // step t's copies: first half issued after the hand-over of step t-2, second half in
+        // sub-step 0 of step t-1; steps 0 and 1 came whole from the prologue.
+        int t = 0;
+        if (ksteps == 1) {
+            k_step(no{}, no{}, yes{}, 0, 0, 0);
+            return;
         }
-        for (; t + 1 < ksteps; ++t) {
-            const int next = stage + 1 == STAGES ? 0 : stage + 1;
-            k_step(no{}, no{}, t, stage, next);
-            stage = next;
+        if (ksteps > 2) k_step(no{}, yes{}, no{}, 0, 0, 1);
+        else k_step(no{}, no{}, no{}, 0, 0, 1);
+        for (t = 1; t + 2 < ksteps; ++t) k_step(yes{}, yes{}, no{}, t, t & 1, (t & 1) ^ 1);
+        if (t + 1 < ksteps) {  // t == ksteps - 2 >= 1: step t+1 >= 2 still needs its second half
+            k_step(yes{}, no{}, no{}, t, t & 1, (t & 1) ^ 1);
+            ++t;
         }
-        k_step(no{}, yes{}, t, stage, stage);
+        k_step(no{}, no{}, yes{}, t, t & 1, t & 1);
     }
 };
 
