@@ -53,10 +53,10 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
     }
     const int esize = p.c_dtype == DT_F32 ? 4 : 2;
     char* c_problem = p.C + static_cast<int64_t>(q.batch) * p.batch_c * esize;
-    const bool inside = m_wave + 32 * MT <= p.M && n_wave + 32 * NT <= p.N;
+    const bool inside = m_wave + lane::kBlock * MT <= p.M && n_wave + lane::kBlock * NT <= p.N;
     if (inside && p.c_vec8 && p.beta == 0.0f && !(p.bias && p.bias_along_m)) {
         // Common case: whole wave tile inside C, aligned rows, nothing to read back.
-        const int n_run = n_wave + 8 * (lane % (4 * NT));
+        const int n_run = n_wave + 8 * (lane % (2 * NT));
         float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (p.bias) {
             const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + n_run);

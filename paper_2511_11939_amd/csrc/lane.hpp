@@ -15,7 +15,6 @@ namespace prism {
 
 using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
 using f16x8 = __attribute__((ext_vector_type(8))) _Float16;
-using f32x16 = __attribute__((ext_vector_type(16))) float;
 using f32x4 = __attribute__((ext_vector_type(4))) float;
 using u32x4 = __attribute__((ext_vector_type(4))) uint32_t;
 using u32x2 = __attribute__((ext_vector_type(2))) uint32_t;
@@ -54,24 +53,30 @@ struct TileLayout {
     }
 };
 
-// One lane's share of a 32-row x 16-k MFMA operand fragment: 8 consecutive k
-// of row (row0 + lane%32), taken from k-chunk (2*ksub + lane/32) of the tile.
+// The matrix instruction works on blocks of kBlock rows by kBlockK k.
+constexpr int kBlock = 16;
+constexpr int kBlockK = 32;
+
+// One lane's share of a 16-row x 32-k MFMA operand fragment: 8 consecutive k
+// of row (row0 + lane%16), taken from k-chunk (4*ksub + lane/16) of the tile.
+// Both operands use the same lane -> k assignment, which is all the matrix
+// instruction needs for the k sum to pair the right elements.
 template <typename T, int BK>
 __device__ __forceinline__ typename Frag<T>::type
 load_fragment(const char* tile, int row0, int ksub, int lane)
 {
-    const int row = row0 + (lane & 31);
-    const int chunk = 2 * ksub + (lane >> 5);
+    const int row = row0 + (lane & 15);
+    const int chunk = 4 * ksub + (lane >> 4);
     const u32x4 raw = *reinterpret_cast<const u32x4*>(tile + TileLayout<BK>::offset(row, chunk));
     return __builtin_bit_cast(typename Frag<T>::type, raw);
 }
 
-// ---- accumulator layout of the 32x32 MFMA -----------------------------------------
+// ---- accumulator layout of the 16x16 MFMA -----------------------------------------
 // With the fragment of the "row" operand r and the "column" operand c,
-// D = r * c^T is spread so that lane l holds column l%32 and, in register i
-// (0..15), row 8*(i/4) + 4*(l/32) + i%4.
-__host__ __device__ constexpr int acc_row(int reg, int lane) { return 8 * (reg >> 2) + 4 * (lane >> 5) + (reg & 3); }
-__host__ __device__ constexpr int acc_col(int lane) { return lane & 31; }
+// D = r * c^T is spread so that lane l holds column l%16 and, in register i
+// (0..3), row 4*(l/16) + i.
+__host__ __device__ constexpr int acc_row(int reg, int lane) { return 4 * (lane >> 4) + reg; }
+__host__ __device__ constexpr int acc_col(int lane) { return lane & 15; }
 
 // ---- output conversion ---------------------------------------------------------
 __device__ __forceinline__ uint16_t to_bf16_bits(float x)

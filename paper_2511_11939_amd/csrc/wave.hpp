@@ -12,54 +12,55 @@
 namespace prism {
 namespace wave {
 
-// D[i][j] += sum_k R[i][k] * C[j][k]  for a 32 x 32 x 16 block.
-// `r` / `c`: each lane's 8 consecutive k of row (lane%32), k-half (lane/32).
-// Result layout: see lane::acc_row / lane::acc_col.
-__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 r, bf16x8 c, f32x16 acc)
+// D[i][j] += sum_k R[i][k] * C[j][k]  for a 16 x 16 x 32 block.
+// `r` / `c`: each lane's 8 consecutive k of row (lane%16), k-quarter (lane/16).
+// Result layout: see lane::acc_row / lane::acc_col.  Of the two bf16 shapes of
+// gfx950 this one needs less energy per multiply-add (a quarter of the
+// accumulator registers are read and written per instruction), and on this
+// power-limited part that shows directly as a higher sustained clock.
+__device__ __forceinline__ f32x4 mfma_16x16x32(bf16x8 r, bf16x8 c, f32x4 acc)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(r, c, acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc, 0, 0, 0);
 }
-__device__ __forceinline__ f32x16 mfma_32x32x16(f16x8 r, f16x8 c, f32x16 acc)
+__device__ __forceinline__ f32x4 mfma_16x16x32(f16x8 r, f16x8 c, f32x4 acc)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(r, c, acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(r, c, acc, 0, 0, 0);
 }
 
-// Register-blocked wave tile: MT x NT accumulator blocks of 32 x 32.  The B
+// Register-blocked wave tile: MT x NT accumulator blocks of 16 x 16.  The B
 // fragment is the MFMA's row operand, so every lane ends up holding runs of
 // four consecutive n for one m, which is what a row-major store wants.
 template <typename T, int MT, int NT>
 struct Tile {
     using frag_t = typename Frag<T>::type;
-    f32x16 acc[MT][NT];
+    f32x4 acc[MT][NT];
 
     __device__ __forceinline__ void clear()
     {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
 
-    // one 16-wide k sub-step over the whole wave tile
+    // one 32-wide k sub-step over the whole wave tile
     __device__ __forceinline__ void mma(const frag_t (&a)[MT], const frag_t (&b)[NT])
     {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < NT; ++j) acc[i][j] = mfma_32x32x16(b[j], a[i], acc[i][j]);
+            for (int j = 0; j < NT; ++j) acc[i][j] = mfma_16x16x32(b[j], a[i], acc[i][j]);
     }
 };
 
 // Fragments of one k sub-step for a wave tile whose first row in the LDS tile
-// is row0: MT (or NT) blocks of 32 rows.
+// is row0: MT (or NT) blocks of 16 rows.
 template <typename T, int BK, int NBLK>
 __device__ __forceinline__ void load_fragments(typename Frag<T>::type (&f)[NBLK], const char* tile,
                                                int row0, int ksub, int lane)
 {
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) f[i] = lane::load_fragment<T, BK>(tile, row0 + 32 * i, ksub, lane);
+    for (int i = 0; i < NBLK; ++i) f[i] = lane::load_fragment<T, BK>(tile, row0 + lane::kBlock * i, ksub, lane);
 }
 
 }  // namespace wave

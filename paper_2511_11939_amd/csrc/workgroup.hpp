@@ -63,39 +63,39 @@ __device__ __forceinline__ void copy_async_16(const char* uniform_base, uint32_t
 
 // Drains one wave's accumulator tile through a private LDS patch so that the
 // values leave the wave as runs of four consecutive n, whole rows at a time
-// (the MFMA leaves each lane with values of 32 different rows).  `patch` must
-// hold kDrainRows x (32*NT + 4) floats, is used by this wave only, and must
+// (the MFMA leaves each lane with values of 16 different rows).  `patch` must
+// hold kDrainRows x (16*NT + 4) floats, is used by this wave only, and must
 // not be in use by anybody else (barrier before the first call).
 // sink(row_in_wave_tile, col_in_wave_tile, f32x4) receives every group once.
-constexpr int kDrainRows = 32;
-constexpr int drain_patch_bytes(int nt) { return kDrainRows * (32 * nt + 4) * 4; }
+// This is the general path (any bounds, any alignment); see drain_runs below.
+constexpr int kDrainRows = 32;  // two 16-row blocks per pass
+constexpr int drain_patch_bytes(int nt) { return kDrainRows * (lane::kBlock * nt + 4) * 4; }
 
 template <int MT, int NT, typename TileT, typename Sink>
 __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, Sink&& sink)
 {
-    constexpr int WTN = 32 * NT;
+    static_assert(MT % 2 == 0, "a pass takes two 16-row blocks");
+    constexpr int WTN = lane::kBlock * NT;
     constexpr int PITCH = WTN + 4;  // floats; +4 shifts consecutive rows by one 16-byte bank group
     constexpr int LANES_PER_ROW = WTN / 4;
-    constexpr int ROWS_PER_ITER = 64 / LANES_PER_ROW;
+    constexpr int ROWS_PER_ITER = 64 / LANES_PER_ROW > 0 ? 64 / LANES_PER_ROW : 1;
     constexpr int ITERS = kDrainRows / ROWS_PER_ITER;
+    static_assert(LANES_PER_ROW <= 64, "one row per wave pass at most");
     float* buf = reinterpret_cast<float*>(patch);
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        float* wr = buf + lane::acc_col(lane) * PITCH;
+    for (int pass = 0; pass < MT / 2; ++pass) {
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+        for (int ii = 0; ii < 2; ++ii) {
+            float* wr = buf + (lane::kBlock * ii + lane::acc_col(lane)) * PITCH + lane::acc_row(0, lane);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x16& a = acc.acc[i][j];
-                *reinterpret_cast<f32x4*>(wr + 32 * j + lane::acc_row(4 * g, lane)) =
-                    f32x4{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
-            }
+            for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4*>(wr + lane::kBlock * j) = acc.acc[2 * pass + ii][j];
+        }
         const int col = 4 * (lane % LANES_PER_ROW);
 #pragma unroll 4
         for (int it = 0; it < ITERS; ++it) {
             const int row = it * ROWS_PER_ITER + lane / LANES_PER_ROW;
             const f32x4 v = *reinterpret_cast<const f32x4*>(buf + row * PITCH + col);
-            sink(32 * i + row, col, v);
+            sink(kDrainRows * pass + row, col, v);
         }
     }
 }
@@ -103,13 +103,14 @@ __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, S
 // Fast drain for a wave tile that lies wholly inside C: the accumulators go to
 // the patch as they are (straight from the accumulator registers), come back as
 // runs of eight consecutive n per lane, and sink(row_in_wave_tile, v_lo, v_hi)
-// finishes and stores each run (columns 8*(lane % (4*NT)) .. +7 of the wave tile).
+// finishes and stores each run (columns 8*(lane % (2*NT)) .. +7 of the wave tile).
 // Inside a patch row the 16-byte units are stored evens first, odds second, so
 // that both the writes and the two reads of a run are spread over all banks.
 template <int MT, int NT, typename TileT, typename Sink>
 __device__ __forceinline__ void drain_runs(const TileT& acc, char* patch, int lane, Sink&& sink)
 {
-    constexpr int WTN = 32 * NT;
+    static_assert(MT % 2 == 0, "a pass takes two 16-row blocks");
+    constexpr int WTN = lane::kBlock * NT;
     constexpr int UNITS = WTN / 4;            // 16-byte units per row
     constexpr int PITCH = (WTN + 4) * 4;      // bytes
     constexpr int LANES_PER_ROW = WTN / 8;
@@ -117,19 +118,16 @@ __device__ __forceinline__ void drain_runs(const TileT& acc, char* patch, int la
     constexpr int ITERS = kDrainRows / ROWS_PER_ITER;
     // unit u of a row sits at position (u >> 1) + (UNITS / 2) * (u & 1)
     const int run = lane % LANES_PER_ROW, sub = lane / LANES_PER_ROW;
+    // this lane's accumulators of block column j are unit 4j + lane/16 of their row
+    const int q = lane >> 4;
+    const int wr_lane = lane::acc_col(lane) * PITCH + 16 * ((q >> 1) + (UNITS / 2) * (q & 1));
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        char* wr = patch + lane::acc_col(lane) * PITCH;
+    for (int pass = 0; pass < MT / 2; ++pass) {
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+        for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x16& a = acc.acc[i][j];
-                // unit 8j + 2g + lane/32 of the row; its parity is lane/32
-                const int pos = 4 * j + g;  // unit_pos without the parity term
-                *reinterpret_cast<f32x4*>(wr + 16 * pos + (lane >> 5) * (UNITS / 2) * 16) =
-                    f32x4{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
-            }
+            for (int j = 0; j < NT; ++j)
+                *reinterpret_cast<f32x4*>(patch + wr_lane + lane::kBlock * ii * PITCH + 32 * j) = acc.acc[2 * pass + ii][j];
         f32x4 lo[ITERS], hi[ITERS];
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
@@ -138,7 +136,7 @@ __device__ __forceinline__ void drain_runs(const TileT& acc, char* patch, int la
             hi[it] = *reinterpret_cast<const f32x4*>(rd + 16 * (run + UNITS / 2));   // unit 2*run+1 -> position run + UNITS/2
         }
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) sink(32 * i + it * ROWS_PER_ITER + sub, lo[it], hi[it]);
+        for (int it = 0; it < ITERS; ++it) sink(kDrainRows * pass + it * ROWS_PER_ITER + sub, lo[it], hi[it]);
         __builtin_amdgcn_sched_barrier(0);  // one pass at a time keeps the register need small
     }
 }
@@ -152,8 +150,8 @@ struct Pipeline {
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-    static constexpr int MT = WTM / 32, NT = WTN / 32;
-    static constexpr int KSUB = BK / 16;
+    static constexpr int MT = WTM / lane::kBlock, NT = WTN / lane::kBlock;
+    static constexpr int KSUB = BK / lane::kBlockK;
     static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
@@ -162,7 +160,7 @@ struct Pipeline {
     static constexpr int COPIES = A_COPIES + B_COPIES;
     static_assert(BM % (COPY_ROWS * NW) == 0 && BN % (COPY_ROWS * NW) == 0, "tile rows must split over the waves");
     static_assert((NW * COPY_ROWS) % 16 == 0, "the swizzle of a lane's row must not depend on the copy index");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of pairs of 16x16 blocks");
     static_assert(LDS_BYTES <= 163840, "LDS budget of one gfx950 compute unit");
     static_assert(NW * drain_patch_bytes(NT) <= LDS_BYTES, "epilogue patches reuse the operand slots");
     static_assert(STAGES >= 2 && (STAGES - 1) * COPIES <= 63, "vmcnt range");
@@ -175,7 +173,7 @@ struct Pipeline {
     // rows of the tile that exist (>= 1; missing rows re-read the last one and
     // their results are never stored).  ksteps >= 1 steps of BK k each.
     //
-    // Schedule of one K step (KSUB sub-steps of 16 k, NM = MT*NT MFMAs each):
+    // Schedule of one K step (KSUB sub-steps of 32 k, NM = MT*NT MFMAs each):
     //   sub-steps 0 .. KSUB-2 : MFMAs of sub-step s, the fragment reads of
     //                           sub-step s+1 dealt one by one between them;
     //   sub-step KSUB-1       : wait for my copies of the next step, barrier,
@@ -225,12 +223,12 @@ struct Pipeline {
         auto read = [&](int r, int buf, int stage, int ksub) {
             const char* st = lds + stage * STAGE_BYTES;
             if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(st, a_row0, ksub, lane);
-            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(st + A_BYTES, b_row0 + 32 * (r - 1), ksub, lane);
-            else fa[buf][r - NT] = lane::load_fragment<T, BK>(st, a_row0 + 32 * (r - NT), ksub, lane);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
+            else fa[buf][r - NT] = lane::load_fragment<T, BK>(st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
         };
         auto mfma = [&](int m, int buf) {
             const int i = m / NT, j = m % NT;
-            acc.acc[i][j] = wave::mfma_32x32x16(fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            acc.acc[i][j] = wave::mfma_16x16x32(fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
 
         // -- prologue: fill the slots, wait for step 0, fetch its first fragments
@@ -247,9 +245,10 @@ struct Pipeline {
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
 
-        // MFMA slot of side instruction number n when `count` of them share the slots
-        // [first, NM) of a group (wrapping round when there are more than slots).
-        auto slot_of = [](int n, int first) constexpr { return first < NM ? first + n % (NM - first) : n % NM; };
+        // MFMA slots of the memory instructions of a group: reads on the even slots, copies on
+        // the odd ones, so no MFMA has more than one of them in its 16-cycle shadow.
+        auto read_slot = [](int r) constexpr { return 2 * r < NM ? 2 * r : r % NM; };
+        auto copy_slot = [](int c) constexpr { return 2 * c + 1 < NM ? 2 * c + 1 : c % NM; };
         constexpr int HALF = COPIES / 2;
 
         // One K step t on slot `stage`.
@@ -270,11 +269,11 @@ struct Pipeline {
                     for (int m = 0; m < NM; ++m) {
 #pragma unroll
                         for (int r = 0; r < NR; ++r)
-                            if (slot_of(r, 0) == m) read(r, nxt, stage, ks + 1);
+                            if (read_slot(r) == m) read(r, nxt, stage, ks + 1);
                         if (HEAD && ks == 0) {
 #pragma unroll
                             for (int c = HALF; c < COPIES; ++c)
-                                if (slot_of(c - HALF, NR) == m) copy(c, t + 1, next);
+                                if (copy_slot(c - HALF) == m) copy(c, t + 1, next);
                         }
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
@@ -290,11 +289,11 @@ struct Pipeline {
                     for (int m = 0; m < NM; ++m) {
 #pragma unroll
                         for (int r = 0; r < NR; ++r)
-                            if (slot_of(r, 0) == m) read(r, nxt, next, 0);
+                            if (read_slot(r) == m) read(r, nxt, next, 0);
                         if (TAIL) {
 #pragma unroll
                             for (int c = 0; c < HALF; ++c)
-                                if (slot_of(c, NR) == m) copy(c, t + 2, stage);
+                                if (copy_slot(c) == m) copy(c, t + 2, stage);
                         }
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
@@ -336,8 +335,8 @@ template <typename T>
 struct Staged {
     using L = lane::TileLayout<64>;
     static constexpr int BM = 128, BN = 128, BK = 64, NW = 4, THREADS = 256;
-    static constexpr int WTM = 64, WTN = 64, MT = 2, NT = 2;
-    static constexpr int KSUB = BK / 16;
+    static constexpr int WTM = 64, WTN = 64, MT = WTM / lane::kBlock, NT = WTN / lane::kBlock;
+    static constexpr int KSUB = BK / lane::kBlockK;
     static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes;
     static constexpr int DRAIN_BYTES = NW * drain_patch_bytes(NT);
     static constexpr int LDS_BYTES = A_BYTES + B_BYTES > DRAIN_BYTES ? A_BYTES + B_BYTES : DRAIN_BYTES;
