@@ -134,23 +134,23 @@ __device__ __forceinline__ void finish4_any(const GemmParams& p, char* c_problem
 
 // Eight consecutive results of one row, no bounds to check and no beta term:
 // scale, add the (pre-loaded) bias, convert, store as one or two 16-byte pieces.
-__device__ __forceinline__ void finish_run(char* dst, int c_dtype, float alpha, const float (&bias)[8], bool plain,
-                                           f32x4 lo, f32x4 hi)
+// With alpha == 1 and a zero bias the arithmetic is exact, so there is no
+// separate path for a plain product.
+template <int OUT>
+__device__ __forceinline__ void finish_run(char* dst, float alpha, const float (&bias)[8], f32x4 lo, f32x4 hi)
 {
     float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    if (!plain) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) o[q] = alpha * o[q] + bias[q];
-    }
-    if (c_dtype == DT_F32) {
+    for (int q = 0; q < 8; ++q) o[q] = alpha * o[q] + bias[q];
+    if constexpr (OUT == DT_F32) {
         reinterpret_cast<f32x4*>(dst)[0] = f32x4{o[0], o[1], o[2], o[3]};
         reinterpret_cast<f32x4*>(dst)[1] = f32x4{o[4], o[5], o[6], o[7]};
     } else {
         uint32_t w[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const uint32_t a = c_dtype == DT_BF16 ? lane::to_bf16_bits(o[2 * q]) : lane::to_f16_bits(o[2 * q]);
-            const uint32_t b = c_dtype == DT_BF16 ? lane::to_bf16_bits(o[2 * q + 1]) : lane::to_f16_bits(o[2 * q + 1]);
+            const uint32_t a = OUT == DT_BF16 ? lane::to_bf16_bits(o[2 * q]) : lane::to_f16_bits(o[2 * q]);
+            const uint32_t b = OUT == DT_BF16 ? lane::to_bf16_bits(o[2 * q + 1]) : lane::to_f16_bits(o[2 * q + 1]);
             w[q] = a | (b << 16);
         }
         *reinterpret_cast<u32x4*>(dst) = u32x4{w[0], w[1], w[2], w[3]};

@@ -3,6 +3,8 @@
 // epilogue.  All arithmetic of the matrix product happens here on the GPU.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "grid.hpp"
 #include "lane.hpp"
 #include "launch.hpp"
@@ -64,12 +66,23 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
             bias[0] = b0[0]; bias[1] = b0[1]; bias[2] = b0[2]; bias[3] = b0[3];
             bias[4] = b1[0]; bias[5] = b1[1]; bias[6] = b1[2]; bias[7] = b1[3];
         }
-        const bool plain = !p.bias && p.alpha == 1.0f;
+        // the bias must be in registers before the first store is issued: stores and loads
+        // share one in-order counter, so a later wait for the bias would wait for stores too
+        wg::wait_counts<0, 15>();
         const int64_t row_bytes = p.ldc * esize;
-        char* dst0 = c_problem + m_wave * row_bytes + static_cast<int64_t>(n_run) * esize;
-        wg::drain_runs<MT, NT>(acc, patch, lane, [&](int r, f32x4 lo, f32x4 hi) {
-            grid::finish_run(dst0 + r * row_bytes, p.c_dtype, p.alpha, bias, plain, lo, hi);
-        });
+        char* tile_base = c_problem + m_wave * row_bytes;                       // uniform
+        const uint32_t lane_off = static_cast<uint32_t>(n_run * esize);         // per lane, plus its row below
+        auto run = [&](auto out_c) {
+            constexpr int OUT = decltype(out_c)::value;
+            wg::drain_runs<MT, NT>(acc, patch, lane, [&](int r_uniform, int r_lane, f32x4 lo, f32x4 hi) {
+                char* row = tile_base + r_uniform * row_bytes;
+                grid::finish_run<OUT>(row + (lane_off + static_cast<uint32_t>(r_lane) * static_cast<uint32_t>(row_bytes)),
+                                      p.alpha, bias, lo, hi);
+            });
+        };
+        if (p.c_dtype == DT_BF16) run(std::integral_constant<int, DT_BF16>{});
+        else if (p.c_dtype == DT_F16) run(std::integral_constant<int, DT_F16>{});
+        else run(std::integral_constant<int, DT_F32>{});
         return;
     }
     wg::drain<MT, NT>(acc, patch, lane,

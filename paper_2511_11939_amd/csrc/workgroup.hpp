@@ -102,8 +102,9 @@ __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, S
 
 // Fast drain for a wave tile that lies wholly inside C: the accumulators go to
 // the patch as they are (straight from the accumulator registers), come back as
-// runs of eight consecutive n per lane, and sink(row_in_wave_tile, v_lo, v_hi)
-// finishes and stores each run (columns 8*(lane % (2*NT)) .. +7 of the wave tile).
+// runs of eight consecutive n per lane, and sink(row_uniform, row_lane, v_lo, v_hi)
+// finishes and stores each run: row row_uniform + row_lane of the wave tile (the
+// first part is the same for all lanes), columns 8*(lane % (2*NT)) .. +7.
 // Inside a patch row the 16-byte units are stored evens first, odds second, so
 // that both the writes and the two reads of a run are spread over all banks.
 template <int MT, int NT, typename TileT, typename Sink>
@@ -136,7 +137,7 @@ __device__ __forceinline__ void drain_runs(const TileT& acc, char* patch, int la
             hi[it] = *reinterpret_cast<const f32x4*>(rd + 16 * (run + UNITS / 2));   // unit 2*run+1 -> position run + UNITS/2
         }
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) sink(kDrainRows * pass + it * ROWS_PER_ITER + sub, lo[it], hi[it]);
+        for (int it = 0; it < ITERS; ++it) sink(kDrainRows * pass + it * ROWS_PER_ITER, sub, lo[it], hi[it]);
         __builtin_amdgcn_sched_barrier(0);  // one pass at a time keeps the register need small
     }
 }
