@@ -31,10 +31,10 @@ namespace lane {
 // ---- LDS tile layout ---------------------------------------------------------
 // An operand tile in LDS is `rows` x BK elements, K contiguous, made of
 // 16-byte chunks (8 elements).  Chunk c of row r is kept at chunk position
-// c ^ swizzle(r).  The swizzles are chosen so that 16 lanes reading the same
-// logical chunk of 16 consecutive rows touch 16 distinct 16-byte bank groups
-// of a 256-byte LDS row (and 8 consecutive rows 8 distinct groups of a
-// 128-byte row): the 128-bit fragment reads are then free of bank conflicts.
+// c ^ swizzle(r).  A 128-bit LDS read is served 16 lanes at a time; with
+// swizzle(r) = r % 8 the 16 lanes of a fragment read (16 consecutive rows, one
+// logical chunk) were measured free of bank conflicts (SQ_LDS_BANK_CONFLICT = 0),
+// for every sub-step and row block of a slot.
 constexpr int kChunkBytes = 16;
 
 template <int BK>
@@ -45,7 +45,7 @@ struct TileLayout {
     static constexpr int kChunksPerRow = kRowBytes / kChunkBytes;
     __host__ __device__ static constexpr int swizzle(int row)
     {
-        return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (((row >> 1) ^ (row >> 2)) & 3);
+        return BK == 64 ? (row & 7) : (((row >> 1) ^ (row >> 2)) & 3);
     }
     __host__ __device__ static constexpr int offset(int row, int chunk)
     {
