@@ -26,6 +26,42 @@ def algorithmic_bytes(w) -> float:
     return w.batch * (w.M * w.K * 2 + w.K * w.N * 2 + w.M * w.N * ESIZE[w.c_dtype]) + (w.N * 4 if w.bias else 0)
 
 
+def source_digest() -> str:
+    """Digest of the kernel sources: measured HBM traffic is only reported for the
+    sources it was measured on."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2511_11939_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (two runs), each divided by the factor the same counter shows on a copy of known size
+# (--calibrate-copy).  Summaries under profiles/.  workload -> (bytes, digest of the sources).
+MEASURED_TRAFFIC: dict = {
+    "cfg2_4096_bf16": (235_242_000, "38ac65afec137c9c"),
+    "cfg3_proj_bias": (940_916_000, "38ac65afec137c9c"),
+    "cfg5_batched_512": (403_015_000, "38ac65afec137c9c"),
+}
+
+
+def calibrate_copy(n_bytes: int, reps: int) -> int:
+    """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    torch.cuda.set_device(0)
+    src = torch.ones(n_bytes // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy_bytes_read": n_bytes, "bytes_written": n_bytes, "reps": reps}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,7 +70,11 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2_4096_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1024, help="output rows the CPU oracle is timed on")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
+                    help="run only a device copy of BYTES (counter calibration under rocprofv3)")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        return calibrate_copy(args.calibrate_copy, args.steps)
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU; --gpus must be 1 "
               "(there is no multi-GPU path to measure)", file=sys.stderr)
@@ -96,8 +136,11 @@ def main() -> int:
         achieved = algorithmic_bytes(w) / (launch_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
-    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined"}.get(plan.kernel, "none")
+    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent"}.get(plan.kernel, "none")
     roofline["launch_us"] = round(launch_ms * 1e3, 2)
+    measured = MEASURED_TRAFFIC.get(w.name)
+    if measured and measured[1] == source_digest():
+        roofline["traffic"] = measured[0]
 
     out = {
         "metric": "bf16 GEMM TFLOP/s and % of MI355X dense bf16 MFMA peak (1 GPU)",

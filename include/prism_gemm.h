@@ -81,14 +81,16 @@ typedef struct prism_gemm_desc {
  */
 typedef struct prism_gemm_plan {
     int32_t kernel;          /* 0 = nothing to launch, 1 = staged (any layout/alignment),
-                                2 = direct-to-LDS pipeline (K-contiguous, aligned)    */
+                                2 = direct-to-LDS pipeline (K-contiguous, aligned),
+                                3 = the same pipeline, persistent over several tiles
+                                    (only with PRISM_PERSISTENT=1 in the environment) */
     int32_t tile_m, tile_n, tile_k; /* workgroup tile                                */
     int32_t waves;           /* wavefronts per workgroup                              */
     int32_t split_k;         /* K slices actually used (>= 1)                         */
     int32_t swapped;         /* 1 if the problem is run as C^T = B^T A^T              */
     int32_t reserved;
     int64_t tiles_m, tiles_n;
-    int64_t workgroups;      /* grid size of the main kernel                          */
+    int64_t workgroups;      /* grid size of the main kernel (kernel 3: at most 256)  */
     size_t workspace_bytes;  /* scratch the chosen split needs (0 when split_k == 1)  */
 } prism_gemm_plan_t;
 

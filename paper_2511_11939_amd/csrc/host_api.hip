@@ -22,7 +22,8 @@ struct Problem {
     GemmParams p;
     prism_gemm_plan_t plan;
     int ab_dtype;
-    int pipe_config;  // index into kPipeConfigs when plan.kernel == 2
+    int pipe_config;  // index into kPipeConfigs when plan.kernel is 2 or 3
+    int total_units;  // (tile, unit) pairs the persistent kernel walks
 };
 
 bool valid_dtype_ab(int v) { return v == PRISM_DTYPE_BF16 || v == PRISM_DTYPE_F16; }
@@ -193,10 +194,23 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     p.tiles_n = static_cast<int>(tiles_n);
 
     plan.tile_m = tile_m; plan.tile_n = tile_n; plan.waves = waves;
-    plan.tile_k = plan.kernel == 2 ? prism::kPipeConfigs[out->pipe_config].tile_k : 64;
+    plan.tile_k = plan.kernel >= 2 ? prism::kPipeConfigs[out->pipe_config].tile_k : 64;
     plan.split_k = static_cast<int32_t>(split);
     plan.tiles_m = tiles_m; plan.tiles_n = tiles_n;
     plan.workgroups = units * split;
+    // Opt-in (PRISM_PERSISTENT=1): tiles of 256x256 whose slices all have two or more K steps go
+    // to the persistent kernel: at most one workgroup per compute unit, each walking several
+    // (tile, unit) pairs.  Off by default: measured slower than one workgroup per tile.
+    {
+        const char* e = std::getenv("PRISM_PERSISTENT");
+        const bool allowed = e && e[0] == '1';
+        const int64_t last_slice_steps = ksteps - (split - 1) * slice_steps;
+        if (allowed && plan.kernel == 2 && out->pipe_config == 0 && slice_steps >= 2 && last_slice_steps >= 2) {
+            plan.kernel = 3;
+            out->total_units = static_cast<int>(units * split);
+            if (plan.workgroups > kComputeUnits) plan.workgroups = kComputeUnits;
+        }
+    }
     plan.workspace_bytes = ws_need;
     if (plan.workgroups > kIntMax) return PRISM_ERR_INVALID_ARG;
     return PRISM_OK;
@@ -207,7 +221,9 @@ prism_status_t run(const Problem& pr, hipStream_t stream)
     const GemmParams& p = pr.p;
     if (p.M == 0 || p.N == 0 || p.batch == 0) return PRISM_OK;
     hipError_t e = hipSuccess;
-    if (pr.plan.kernel == 2)
+    if (pr.plan.kernel == 3)
+        e = prism::launch_persistent(pr.ab_dtype, p, pr.total_units, static_cast<int>(pr.plan.workgroups), stream);
+    else if (pr.plan.kernel == 2)
         e = prism::launch_pipelined(pr.pipe_config, pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);
     else if (pr.plan.kernel == 1)
         e = prism::launch_staged(pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);

@@ -39,18 +39,26 @@ __device__ __forceinline__ Placement place(const GemmParams& p, int wg)
     return q;
 }
 
-// Accumulators of one wave tile -> C or the split-K scratch.  Workgroup-collective:
-// every wave must call it (it starts with a barrier that retires the operand slots).
-template <typename TileT, int MT, int NT>
+// Accumulators of one wave tile -> C or the split-K scratch.
+// OWN_PATCH false: the patches reuse the operand slots; workgroup-collective, every wave
+// must call it (it starts with a barrier that retires the slots).  OWN_PATCH true: `patch`
+// is this wave's private 16-row patch outside the slots; no barrier, 16 rows per pass.
+template <typename TileT, int MT, int NT, bool OWN_PATCH = false>
 __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q, const TileT& acc,
                                          int m_wave, int n_wave, char* lds, int wave, int lane)
 {
-    __syncthreads();
-    char* patch = lds + wave * wg::drain_patch_bytes(NT);
+    char* patch = lds;
+    if constexpr (!OWN_PATCH) {
+        __syncthreads();
+        patch = lds + wave * wg::drain_patch_bytes(NT);
+    }
+    auto drain_any = [&](auto&& sink) {
+        if constexpr (OWN_PATCH) wg::drain<MT, NT, 16, 0>(acc, patch, lane, sink);
+        else wg::drain<MT, NT>(acc, patch, lane, sink);
+    };
     if (p.split_k > 1) {
         float* slab = p.partial + (static_cast<int64_t>(q.batch) * p.split_k + q.slice) * p.M * p.N;
-        wg::drain<MT, NT>(acc, patch, lane,
-                          [&](int r, int c, f32x4 v) { grid::partial4(p, slab, m_wave + r, n_wave + c, v); });
+        drain_any([&](int r, int c, f32x4 v) { grid::partial4(p, slab, m_wave + r, n_wave + c, v); });
         return;
     }
     const int esize = p.c_dtype == DT_F32 ? 4 : 2;
@@ -74,19 +82,20 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
         const uint32_t lane_off = static_cast<uint32_t>(n_run * esize);         // per lane, plus its row below
         auto run = [&](auto out_c) {
             constexpr int OUT = decltype(out_c)::value;
-            wg::drain_runs<MT, NT>(acc, patch, lane, [&](int r_uniform, int r_lane, f32x4 lo, f32x4 hi) {
+            auto sink = [&](int r_uniform, int r_lane, f32x4 lo, f32x4 hi) {
                 char* row = tile_base + r_uniform * row_bytes;
                 grid::finish_run<OUT>(row + (lane_off + static_cast<uint32_t>(r_lane) * static_cast<uint32_t>(row_bytes)),
                                       p.alpha, bias, lo, hi);
-            });
+            };
+            if constexpr (OWN_PATCH) wg::drain_runs16<MT, NT>(acc, patch, lane, sink);
+            else wg::drain_runs<MT, NT>(acc, patch, lane, sink);
         };
         if (p.c_dtype == DT_BF16) run(std::integral_constant<int, DT_BF16>{});
         else if (p.c_dtype == DT_F16) run(std::integral_constant<int, DT_F16>{});
         else run(std::integral_constant<int, DT_F32>{});
         return;
     }
-    wg::drain<MT, NT>(acc, patch, lane,
-                      [&](int r, int c, f32x4 v) { grid::finish4_any(p, c_problem, m_wave + r, n_wave + c, v); });
+    drain_any([&](int r, int c, f32x4 v) { grid::finish4_any(p, c_problem, m_wave + r, n_wave + c, v); });
 }
 
 template <typename P, int BM, int BN, int BK, int WAVES_N>
@@ -109,6 +118,49 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
 
     epilogue<typename P::tile_t, P::MT, P::NT>(p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
                                                q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane);
+}
+
+// Persistent form for the 256x256x64 tile: workgroup w takes tiles w, w + gridDim.x, ...
+// and streams their K steps through wg::PersistentPipe.  Every unit must have at least
+// two K steps (the host guarantees it).
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const int total)
+{
+    using P = wg::PersistentPipe<T>;
+    __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    auto source = [&](const Placement& q) {
+        typename P::Source s;
+        s.a = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm + q.k_begin);
+        s.b = p.B + 2 * (q.batch * p.batch_b + q.n0 * p.b_sn + q.k_begin);
+        s.a_ld = static_cast<uint32_t>(2 * p.a_sm);
+        s.b_ld = static_cast<uint32_t>(2 * p.b_sn);
+        s.a_rows = p.M - q.m0 < P::BM ? p.M - q.m0 : P::BM;
+        s.b_rows = p.N - q.n0 < P::BN ? p.N - q.n0 : P::BN;
+        return s;
+    };
+    int tile = blockIdx.x;
+    Placement cur = place<P::BM, P::BN>(p, tile), nxt = cur;
+    P::run(
+        lds, wave, lane, source(cur), (cur.k_end - cur.k_begin) / P::BK,
+        [&](typename P::Source& s, int& ksteps) {
+            if (tile + static_cast<int>(gridDim.x) >= total) return false;
+            nxt = place<P::BM, P::BN>(p, tile + gridDim.x);
+            s = source(nxt);
+            ksteps = (nxt.k_end - nxt.k_begin) / P::BK;
+            return true;
+        },
+        [&](typename P::tile_t& acc) {
+            epilogue<typename P::tile_t, P::MT, P::NT, true>(p, cur, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
+                                                             cur.n0 + (wave % P::WAVES_N) * P::WTN,
+                                                             lds + P::PATCH_BASE + wave * P::PATCH_BYTES, wave, lane);
+        },
+        [&]() {
+            cur = nxt;
+            tile += gridDim.x;
+        });
 }
 
 template <typename T>
@@ -189,6 +241,15 @@ hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int w
 {
     return ab_dtype == DT_BF16 ? launch_pipe_config<bf16_t>(config, p, workgroups, stream)
                                : launch_pipe_config<f16_t>(config, p, workgroups, stream);
+}
+
+hipError_t launch_persistent(int ab_dtype, const GemmParams& p, int total, int workgroups, hipStream_t stream)
+{
+    if (ab_dtype == DT_BF16)
+        hipLaunchKernelGGL(gemm_persistent<bf16_t>, dim3(workgroups), dim3(256), 0, stream, p, total);
+    else
+        hipLaunchKernelGGL(gemm_persistent<f16_t>, dim3(workgroups), dim3(256), 0, stream, p, total);
+    return hipGetLastError();
 }
 
 hipError_t launch_staged(int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream)

@@ -22,6 +22,9 @@ constexpr int kStagedTileM = 128, kStagedTileN = 128, kStagedWaves = 4;
 // `workgroups` = p.tiles_m * p.tiles_n * p.batch * p.split_k.
 hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream);
 hipError_t launch_staged(int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream);
+// 256x256x64 tile, `workgroups` persistent workgroups walking `total` (tile, unit) pairs;
+// every unit must span at least two K steps of 64.
+hipError_t launch_persistent(int ab_dtype, const GemmParams& p, int total, int workgroups, hipStream_t stream);
 // Sums the split_k partial slabs in slice order and applies the epilogue; with
 // p.split_k == 0 it writes C <- bias + beta*C (the K == 0 case).
 hipError_t launch_reduce(const GemmParams& p, hipStream_t stream);

@@ -71,31 +71,34 @@ __device__ __forceinline__ void copy_async_16(const char* uniform_base, uint32_t
 constexpr int kDrainRows = 32;  // two 16-row blocks per pass
 constexpr int drain_patch_bytes(int nt) { return kDrainRows * (lane::kBlock * nt + 4) * 4; }
 
-template <int MT, int NT, typename TileT, typename Sink>
+// ROWS: rows per pass (32 = two blocks, 16 = one); PAD: floats of row padding (4 keeps the
+// accesses free of bank conflicts, 0 fits 16 rows of a 128-wide tile into 8 KiB).
+template <int MT, int NT, int ROWS = kDrainRows, int PAD = 4, typename TileT, typename Sink>
 __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, Sink&& sink)
 {
-    static_assert(MT % 2 == 0, "a pass takes two 16-row blocks");
+    static_assert(ROWS == 16 || (ROWS == 32 && MT % 2 == 0), "a pass takes one or two 16-row blocks");
+    constexpr int BLOCKS = ROWS / lane::kBlock;
     constexpr int WTN = lane::kBlock * NT;
-    constexpr int PITCH = WTN + 4;  // floats; +4 shifts consecutive rows by one 16-byte bank group
+    constexpr int PITCH = WTN + PAD;  // floats
     constexpr int LANES_PER_ROW = WTN / 4;
     constexpr int ROWS_PER_ITER = 64 / LANES_PER_ROW > 0 ? 64 / LANES_PER_ROW : 1;
-    constexpr int ITERS = kDrainRows / ROWS_PER_ITER;
+    constexpr int ITERS = ROWS / ROWS_PER_ITER;
     static_assert(LANES_PER_ROW <= 64, "one row per wave pass at most");
     float* buf = reinterpret_cast<float*>(patch);
 #pragma unroll
-    for (int pass = 0; pass < MT / 2; ++pass) {
+    for (int pass = 0; pass < MT / BLOCKS; ++pass) {
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
+        for (int ii = 0; ii < BLOCKS; ++ii) {
             float* wr = buf + (lane::kBlock * ii + lane::acc_col(lane)) * PITCH + lane::acc_row(0, lane);
 #pragma unroll
-            for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4*>(wr + lane::kBlock * j) = acc.acc[2 * pass + ii][j];
+            for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4*>(wr + lane::kBlock * j) = acc.acc[BLOCKS * pass + ii][j];
         }
         const int col = 4 * (lane % LANES_PER_ROW);
 #pragma unroll 4
         for (int it = 0; it < ITERS; ++it) {
             const int row = it * ROWS_PER_ITER + lane / LANES_PER_ROW;
             const f32x4 v = *reinterpret_cast<const f32x4*>(buf + row * PITCH + col);
-            sink(kDrainRows * pass + row, col, v);
+            sink(ROWS * pass + row, col, v);
         }
     }
 }
@@ -325,6 +328,234 @@ struct Pipeline {
             ++t;
         }
         k_step(no{}, no{}, yes{}, t, t & 1, t & 1);
+    }
+};
+
+// drain_runs with one 16-row block per pass and no padding: the patch is 16 rows of
+// 16*NT floats (8 KiB for a 128-wide wave tile).  Instead of padding, the 16-byte unit at
+// position p of row r is kept at position p ^ r (positions as in drain_runs: even units
+// first), which spreads the 16 rows of a write and the 16 units of a read over the banks.
+template <int MT, int NT, typename TileT, typename Sink>
+__device__ __forceinline__ void drain_runs16(const TileT& acc, char* patch, int lane, Sink&& sink)
+{
+    constexpr int WTN = lane::kBlock * NT;
+    constexpr int UNITS = WTN / 4;
+    constexpr int PITCH = WTN * 4;            // bytes
+    constexpr int LANES_PER_ROW = WTN / 8;
+    constexpr int ROWS_PER_ITER = 64 / LANES_PER_ROW;
+    constexpr int ITERS = lane::kBlock / ROWS_PER_ITER;
+    static_assert(UNITS / 2 >= 16 || UNITS / 2 == 8, "the row index is folded into the low position bits");
+    constexpr int FOLD = UNITS / 2 >= 16 ? 15 : 7;  // bits of the row folded into the position
+    const int run = lane % LANES_PER_ROW, sub = lane / LANES_PER_ROW;
+    const int q = lane >> 4, r = lane::acc_col(lane);
+    const int pos_q = (q >> 1) + (UNITS / 2) * (q & 1);  // plus 2j for block column j
+    char* wr = patch + r * PITCH;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            *reinterpret_cast<f32x4*>(wr + 16 * ((pos_q + 2 * j) ^ (r & FOLD))) = acc.acc[i][j];
+        f32x4 lo[ITERS], hi[ITERS];
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int row = it * ROWS_PER_ITER + sub;
+            const char* rd = patch + row * PITCH;
+            lo[it] = *reinterpret_cast<const f32x4*>(rd + 16 * (run ^ (row & FOLD)));
+            hi[it] = *reinterpret_cast<const f32x4*>(rd + 16 * ((run + UNITS / 2) ^ (row & FOLD)));
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) sink(lane::kBlock * i + it * ROWS_PER_ITER, sub, lo[it], hi[it]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Persistent form of the pipeline: one workgroup walks a sequence of 256x256 tiles and
+// treats their K steps as one stream.  The copies issued in the last two steps of a tile
+// already belong to the next tile, so its first operands sit in LDS when its first MFMA
+// issues, and the fixed cost of starting a tile (first loads from memory) disappears for
+// every tile but the first.  This is the tile loop of the paper's persistent hgemm kernel
+// (code appendix, `while(true)` over tiles) with the loads of the next tile pipelined
+// under the tail of the current one.
+//
+// LDS: two operand slots (128 KiB) and, behind them, one 8 KiB epilogue patch per wave,
+// which together are exactly the 160 KiB of a compute unit; the patches are separate so
+// that the epilogue of a tile can run while the slots already hold the next tile.
+// ------------------------------------------------------------------------------------
+template <typename T>
+struct PersistentPipe {
+    using L = lane::TileLayout<64>;
+    static constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2, NW = 4, THREADS = 256;
+    static constexpr int WTM = 128, WTN = 128, MT = WTM / lane::kBlock, NT = WTN / lane::kBlock;
+    static constexpr int KSUB = BK / lane::kBlockK, NM = MT * NT, NR = MT + NT;
+    static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int PATCH_BYTES = lane::kBlock * WTN * 4;
+    static constexpr int PATCH_BASE = 2 * STAGE_BYTES;
+    static constexpr int LDS_BYTES = PATCH_BASE + NW * PATCH_BYTES;
+    static constexpr int COPY_ROWS = 8, A_COPIES = BM / COPY_ROWS / NW, COPIES = 2 * A_COPIES, HALF = COPIES / 2;
+    static_assert(LDS_BYTES <= 163840 && KSUB == 2 && BM == BN, "written for the 256x256x64 tile");
+
+    using tile_t = wave::Tile<T, MT, NT>;
+    using frag_t = typename Frag<T>::type;
+
+    // Operand rows of one tile: a / b point at (first row of the tile, first k of the slice).
+    struct Source {
+        const char* a;
+        const char* b;
+        uint32_t a_ld, b_ld;  // row pitch in bytes
+        int a_rows, b_rows;   // rows that exist (>= 1)
+    };
+
+    // Walks the tiles of one workgroup.
+    //   first / first_ksteps: operands and K steps (>= 2) of the first tile
+    //   peek(Source&, int& ksteps) -> bool: describes the tile after the current one, false if none
+    //   finish(tile_t&): epilogue of the current tile (its accumulators are complete)
+    //   advance(): the tile described by the last peek becomes the current one
+    template <typename Peek, typename Finish, typename Advance>
+    __device__ __forceinline__ static void run(char* lds, int wave, int lane, Source first, int first_ksteps,
+                                               Peek&& peek, Finish&& finish, Advance&& advance)
+    {
+        tile_t acc;
+        frag_t fa[2][MT], fb[2][NT];
+        uint32_t g_off[COPIES];
+        const uint32_t lds0 = lds_address(lds) + wave * 1024;
+        const int a_row0 = (wave / WAVES_N) * WTM, b_row0 = (wave % WAVES_N) * WTN;
+
+        // per-lane copy offsets for a tile (rows beyond the matrix re-read the last row)
+        auto set_offsets = [&](const Source& s) {
+            const int sub_row = lane / L::kChunksPerRow;
+            const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
+#pragma unroll
+            for (int i = 0; i < A_COPIES; ++i) {
+                const int row = (i * NW + wave) * COPY_ROWS + sub_row;
+                const int ra = row < s.a_rows ? row : s.a_rows - 1;
+                const int rb = row < s.b_rows ? row : s.b_rows - 1;
+                g_off[i] = static_cast<uint32_t>(ra) * s.a_ld + chunk * lane::kChunkBytes;
+                g_off[A_COPIES + i] = static_cast<uint32_t>(rb) * s.b_ld + chunk * lane::kChunkBytes;
+            }
+        };
+        // copy number c of the K step whose operands start at a_src / b_src, into slot `stage`
+        auto copy = [&](int c, const char* a_src, const char* b_src, int stage) {
+            const uint32_t slot = lds0 + stage * STAGE_BYTES;
+            if (c < A_COPIES) copy_async_16(a_src, g_off[c], slot + c * NW * 1024);
+            else copy_async_16(b_src, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
+        };
+        auto read = [&](int r, int buf, int stage, int ksub) {
+            const char* st = lds + stage * STAGE_BYTES;
+            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(st, a_row0, ksub, lane);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
+            else fa[buf][r - NT] = lane::load_fragment<T, BK>(st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
+        };
+        auto mfma = [&](int m, int buf) {
+            const int i = m / NT, j = m % NT;
+            acc.acc[i][j] = wave::mfma_16x16x32(fb[buf][j], fa[buf][i], acc.acc[i][j]);
+        };
+        auto read_slot = [](int r) constexpr { return 2 * r; };
+        auto copy_slot = [](int c) constexpr { return 2 * c + 1; };
+
+        // One K step computing from slot `stage`.  Compile-time: HEAD (second half of the copies
+        // of the next step, from a1 / b1, into the other slot).  Run-time, for the last two steps
+        // of a tile only (RT): head, handover (a step follows: barrier + its first fragments),
+        // tail (first half of the copies of the step after next, from a2 / b2, into this slot),
+        // do_switch (load the copy offsets of tile switch_to between the two halves).
+        auto k_step = [&](auto rt_c, auto head_c, int stage, bool head, const char* a1, const char* b1,
+                          bool do_switch, const Source& switch_to, bool handover, bool tail, const char* a2,
+                          const char* b2) {
+            constexpr bool RT = decltype(rt_c)::value;
+            constexpr bool HEAD = decltype(head_c)::value;
+            const int next = stage ^ 1;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+#pragma unroll
+                for (int r = 0; r < NR; ++r)
+                    if (read_slot(r) == m) read(r, 1, stage, 1);
+                if (RT ? head : HEAD) {
+#pragma unroll
+                    for (int c = HALF; c < COPIES; ++c)
+                        if (copy_slot(c - HALF) == m) copy(c, a1, b1, next);
+                }
+                mfma(m, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (RT && do_switch) set_offsets(switch_to);
+            if (!RT || handover) {
+                wait_counts<0, 0>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+#pragma unroll
+                    for (int r = 0; r < NR; ++r)
+                        if (read_slot(r) == m) read(r, 0, next, 0);
+                    if (!RT || tail) {
+#pragma unroll
+                        for (int c = 0; c < HALF; ++c)
+                            if (copy_slot(c) == m) copy(c, a2, b2, stage);
+                    }
+                    mfma(m, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int m = 0; m < NM; ++m) mfma(m, 1);
+            }
+        };
+        using yes = std::integral_constant<bool, true>;
+        using no = std::integral_constant<bool, false>;
+        constexpr int STEP = L::kRowBytes;  // bytes one K step advances in a row
+
+        // -- first tile: steps 0 and 1 whole, then the first fragments
+        Source sc = first;
+        int ksteps = first_ksteps;
+        set_offsets(sc);
+#pragma unroll
+        for (int c = 0; c < COPIES; ++c) copy(c, sc.a, sc.b, 0);
+#pragma unroll
+        for (int c = 0; c < COPIES; ++c) copy(c, sc.a + STEP, sc.b + STEP, 1);
+        wait_counts<COPIES, 0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
+
+        int stage = 0;
+        bool first_tile = true;
+        for (;;) {
+            Source sn = sc;
+            int next_ksteps = 0;
+            const bool has_next = peek(sn, next_ksteps);
+            acc.clear();
+            int t = 0;
+            if (ksteps >= 3) {
+                // steps 0 .. ksteps-3: everything they copy belongs to this tile
+                if (first_tile) k_step(no{}, no{}, stage, false, sc.a + STEP, sc.b + STEP, false, sc, true, true, sc.a + 2 * STEP, sc.b + 2 * STEP);
+                else k_step(no{}, yes{}, stage, true, sc.a + STEP, sc.b + STEP, false, sc, true, true, sc.a + 2 * STEP, sc.b + 2 * STEP);
+                stage ^= 1;
+                for (t = 1; t + 3 <= ksteps; ++t) {
+                    const int64_t o = static_cast<int64_t>(t) * STEP;
+                    k_step(no{}, yes{}, stage, true, sc.a + o + STEP, sc.b + o + STEP, false, sc, true, true,
+                           sc.a + o + 2 * STEP, sc.b + o + 2 * STEP);
+                    stage ^= 1;
+                }
+            }
+            {   // step ksteps-2: second half of the last step; first half of the next tile's step 0
+                const int64_t o = static_cast<int64_t>(ksteps - 1) * STEP;
+                k_step(yes{}, no{}, stage, !(first_tile && t == 0), sc.a + o, sc.b + o, has_next, sn, true, has_next,
+                       sn.a, sn.b);
+                stage ^= 1;
+            }
+            // step ksteps-1: second half of the next tile's step 0, first half of its step 1
+            k_step(yes{}, no{}, stage, has_next, sn.a, sn.b, false, sn, has_next, has_next, sn.a + STEP, sn.b + STEP);
+            stage ^= 1;
+
+            finish(acc);
+            if (!has_next) break;
+            advance();
+            sc = sn;
+            ksteps = next_ksteps;
+            first_tile = false;
+        }
     }
 };
 

@@ -271,6 +271,18 @@ def test_pipeline_short_k_loops(ksteps, monkeypatch):
         _general_case(256, 256, 64 * ksteps, ints=True)
 
 
+@pytest.mark.parametrize("M,N,K,batch,split", [(512, 768, 128, 1, 0), (520, 600, 192, 1, 0), (1024, 2304, 448, 1, 0),
+                                               (512, 512, 1024, 1, 3), (512, 512, 256, 40, 0), (4352, 4352, 128, 1, 0)])
+def test_persistent_kernel_opt_in(M, N, K, batch, split, monkeypatch):
+    """The persistent variant of the pipeline (several tiles per workgroup) is opt-in."""
+    monkeypatch.setenv("PRISM_PERSISTENT", "1")
+    desc = P.make_desc(c_dtype="f32")
+    s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, M * K, None, K, K * N, None, N, M * N, batch)
+    assert s == 0 and plan.kernel == 3 and plan.workgroups <= 256
+    _general_case(M, N, K, ints=True, batch=batch, split_k=split)
+    _general_case(M, N, K, ab="f16", cd="bf16", bias=True, alpha=-1.25, batch=batch, split_k=split)
+
+
 def test_unaligned_pointers_and_odd_ld():
     _general_case(96, 80, 128, pad=(1, 1, 1), offset=1, bias=True)
     _general_case(96, 80, 128, pad=(0, 0, 0), offset=3, cd="bf16")
