@@ -42,9 +42,9 @@ def source_digest() -> str:
 # (two runs), each divided by the factor the same counter shows on a copy of known size
 # (--calibrate-copy).  Summaries under profiles/.  workload -> (bytes, digest of the sources).
 MEASURED_TRAFFIC: dict = {
-    "cfg2_4096_bf16": (235_242_000, "38ac65afec137c9c"),
-    "cfg3_proj_bias": (940_916_000, "38ac65afec137c9c"),
-    "cfg5_batched_512": (403_015_000, "38ac65afec137c9c"),
+    "cfg2_4096_bf16": (235237885, "97a5f149f3f255e8"),
+    "cfg3_proj_bias": (941252150, "97a5f149f3f255e8"),
+    "cfg5_batched_512": (417631814, "97a5f149f3f255e8"),
 }
 
 
@@ -69,7 +69,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2_4096_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=1024, help="output rows the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="output rows the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
                     help="run only a device copy of BYTES (counter calibration under rocprofv3)")
     args = ap.parse_args()

@@ -82,8 +82,8 @@ typedef struct prism_gemm_desc {
 typedef struct prism_gemm_plan {
     int32_t kernel;          /* 0 = nothing to launch, 1 = staged (any layout/alignment),
                                 2 = direct-to-LDS pipeline (K-contiguous, aligned),
-                                3 = the same pipeline, persistent over several tiles
-                                    (only with PRISM_PERSISTENT=1 in the environment) */
+                                3 = the same pipeline, persistent: used for more tiles
+                                    than compute units with short K loops              */
     int32_t tile_m, tile_n, tile_k; /* workgroup tile                                */
     int32_t waves;           /* wavefronts per workgroup                              */
     int32_t split_k;         /* K slices actually used (>= 1)                         */

@@ -15,6 +15,7 @@ namespace {
 using prism::GemmParams;
 
 constexpr int kComputeUnits = 256;
+constexpr int kPersistentMaxSteps = 16;  // longest K loop (in steps of 64) the persistent kernel is chosen for
 constexpr int kMaxSplit = 64;
 constexpr int64_t kIntMax = 2147483647;
 
@@ -156,7 +157,7 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         if (cfg < 0) {
             // Big tiles when they still give most compute units a workgroup, else small ones.
             const int64_t big = ceil_div(p.M, 256) * ceil_div(p.N, 256) * batch;
-            cfg = (big >= kComputeUnits / 2 || (p.M >= 512 && p.N >= 512)) ? 0 : 2;
+            cfg = (big >= kComputeUnits / 2 || (p.M >= 512 && p.N >= 512)) ? 0 : 1;
         }
         out->pipe_config = cfg;
         tile_m = prism::kPipeConfigs[cfg].tile_m;
@@ -198,14 +199,19 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     plan.split_k = static_cast<int32_t>(split);
     plan.tiles_m = tiles_m; plan.tiles_n = tiles_n;
     plan.workgroups = units * split;
-    // Opt-in (PRISM_PERSISTENT=1): tiles of 256x256 whose slices all have two or more K steps go
-    // to the persistent kernel: at most one workgroup per compute unit, each walking several
-    // (tile, unit) pairs.  Off by default: measured slower than one workgroup per tile.
+    // More (tile, unit) pairs than compute units, each with a short K loop: 256x256 tiles whose
+    // slices all have two or more K steps go to the persistent kernel, one workgroup per
+    // compute unit walking several pairs with the next pair's operands loaded under the tail of
+    // the current one.  With long K loops the start of a tile is a small share of its time and
+    // the hardware's own dealing of workgroups to free compute units balances better than the
+    // fixed assignment of the persistent kernel (measured).
     {
-        const char* e = std::getenv("PRISM_PERSISTENT");
-        const bool allowed = e && e[0] == '1';
+        const char* e = std::getenv("PRISM_PERSISTENT");  // experiment hook: 0 = never, 1 = whenever possible
+        const bool never = e && e[0] == '0', always = e && e[0] == '1';
         const int64_t last_slice_steps = ksteps - (split - 1) * slice_steps;
-        if (allowed && plan.kernel == 2 && out->pipe_config == 0 && slice_steps >= 2 && last_slice_steps >= 2) {
+        const bool possible = plan.kernel == 2 && out->pipe_config == 0 && slice_steps >= 2 && last_slice_steps >= 2;
+        const bool pays = units * split > kComputeUnits && slice_steps <= kPersistentMaxSteps;
+        if (possible && !never && (always || pays)) {
             plan.kernel = 3;
             out->total_units = static_cast<int>(units * split);
             if (plan.workgroups > kComputeUnits) plan.workgroups = kComputeUnits;

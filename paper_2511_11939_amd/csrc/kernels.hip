@@ -15,8 +15,7 @@ namespace prism {
 
 const PipeConfig kPipeConfigs[kNumPipeConfigs] = {
     {0, 256, 256, 64, 4, 2, "256x256x64_w4"},
-    {1, 256, 256, 64, 8, 2, "256x256x64_w8"},
-    {2, 128, 128, 64, 4, 2, "128x128x64_w4"},
+    {1, 128, 128, 64, 4, 2, "128x128x64_w4"},
 };
 
 namespace {
@@ -153,9 +152,13 @@ __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const
             return true;
         },
         [&](typename P::tile_t& acc) {
+            // The epilogue's per-lane addressing is recomputed for every tile: kept live across
+            // the K loop it would not fit in registers beside the accumulators and fragments.
+            int lane_now = lane;
+            asm volatile("" : "+v"(lane_now));
             epilogue<typename P::tile_t, P::MT, P::NT, true>(p, cur, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
                                                              cur.n0 + (wave % P::WAVES_N) * P::WTN,
-                                                             lds + P::PATCH_BASE + wave * P::PATCH_BYTES, wave, lane);
+                                                             lds + P::PATCH_BASE + wave * P::PATCH_BYTES, wave, lane_now);
         },
         [&]() {
             cur = nxt;
@@ -229,8 +232,7 @@ hipError_t launch_pipe_config(int config, const GemmParams& p, int workgroups, h
 {
     switch (config) {
     case 0: return launch_pipe<wg::Pipeline<T, 256, 256, 64, 2, 2, 2>, 256, 256, 64, 2>(p, workgroups, stream);
-    case 1: return launch_pipe<wg::Pipeline<T, 256, 256, 64, 2, 4, 2>, 256, 256, 64, 4>(p, workgroups, stream);
-    case 2: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2>, 128, 128, 64, 2>(p, workgroups, stream);
+    case 1: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2>, 128, 128, 64, 2>(p, workgroups, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -13,7 +13,7 @@ struct PipeConfig {
     int tile_m, tile_n, tile_k, waves, stages;
     const char* name;
 };
-constexpr int kNumPipeConfigs = 3;
+constexpr int kNumPipeConfigs = 2;
 extern const PipeConfig kPipeConfigs[kNumPipeConfigs];
 
 constexpr int kStagedTileM = 128, kStagedTileN = 128, kStagedWaves = 4;

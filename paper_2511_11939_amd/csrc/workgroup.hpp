@@ -253,14 +253,20 @@ struct Pipeline {
         // the odd ones, so no MFMA has more than one of them in its 16-cycle shadow.
         auto read_slot = [](int r) constexpr { return 2 * r < NM ? 2 * r : r % NM; };
         auto copy_slot = [](int c) constexpr { return 2 * c + 1 < NM ? 2 * c + 1 : c % NM; };
-        constexpr int HALF = COPIES / 2;
+        // The first TAILN copies of a step are issued right after the slot is released, one
+        // every TAIL_SPACING MFMAs; the last HEADN at the start of the following step.
+        constexpr int HEADN = COPIES / 4, TAILN = COPIES - HEADN;
+        constexpr int TAIL_SPACING = (NM - 2) / TAILN >= 4 ? 4 : ((NM - 2) / TAILN >= 2 ? 2 : 1);
+        auto tail_slot = [](int c) constexpr { return (TAIL_SPACING * c + 1) % NM; };
 
         // One K step t on slot `stage`.
-        //   HEAD: the second half of the copies of step t+1 is issued in sub-step 0
-        //   TAIL: the first half of the copies of step t+2 is issued after the hand-over
+        //   HEAD: the last HEADN copies of step t+1 are issued in sub-step 0
+        //   TAIL: the first TAILN copies of step t+2 are issued after the hand-over
         //   LAST: no step follows (no hand-over)
-        // Splitting the copies over two groups keeps every MFMA slot down to one memory
-        // instruction, which is what a single wave can issue in the shadow of one MFMA.
+        // Issuing most copies as early as the slot allows gives them a whole K step to land
+        // (rows 16 KiB apart miss the L2 and the address translation caches far more often
+        // than the MFMAs of half a step can hide); spreading them keeps every MFMA slot down
+        // to one memory instruction, which is what a wave can issue in the shadow of one MFMA.
         auto k_step = [&](auto head_c, auto tail_c, auto last_c, int t, int stage, int next) {
             constexpr bool HEAD = decltype(head_c)::value;
             constexpr bool TAIL = decltype(tail_c)::value;
@@ -276,8 +282,8 @@ struct Pipeline {
                             if (read_slot(r) == m) read(r, nxt, stage, ks + 1);
                         if (HEAD && ks == 0) {
 #pragma unroll
-                            for (int c = HALF; c < COPIES; ++c)
-                                if (copy_slot(c - HALF) == m) copy(c, t + 1, next);
+                            for (int c = TAILN; c < COPIES; ++c)
+                                if (copy_slot(c - TAILN) == m) copy(c, t + 1, next);
                         }
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
@@ -296,8 +302,8 @@ struct Pipeline {
                             if (read_slot(r) == m) read(r, nxt, next, 0);
                         if (TAIL) {
 #pragma unroll
-                            for (int c = 0; c < HALF; ++c)
-                                if (copy_slot(c) == m) copy(c, t + 2, stage);
+                            for (int c = 0; c < TAILN; ++c)
+                                if (tail_slot(c) == m) copy(c, t + 2, stage);
                         }
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
@@ -313,7 +319,7 @@ struct Pipeline {
 
         using yes = std::integral_constant<bool, true>;
         using no = std::integral_constant<bool, false>;
-        // step t's copies: first half issued after the hand-over of step t-2, second half in
+        // step t's copies: the first TAILN issued after the hand-over of step t-2, the rest in
         // sub-step 0 of step t-1; steps 0 and 1 came whole from the prologue.
         int t = 0;
         if (ksteps == 1) {
@@ -382,7 +388,7 @@ __device__ __forceinline__ void drain_runs16(const TileT& acc, char* patch, int 
 // which together are exactly the 160 KiB of a compute unit; the patches are separate so
 // that the epilogue of a tile can run while the slots already hold the next tile.
 // ------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int HEADN = 4>
 struct PersistentPipe {
     using L = lane::TileLayout<64>;
     static constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2, NW = 4, THREADS = 256;
@@ -392,7 +398,9 @@ struct PersistentPipe {
     static constexpr int PATCH_BYTES = lane::kBlock * WTN * 4;
     static constexpr int PATCH_BASE = 2 * STAGE_BYTES;
     static constexpr int LDS_BYTES = PATCH_BASE + NW * PATCH_BYTES;
-    static constexpr int COPY_ROWS = 8, A_COPIES = BM / COPY_ROWS / NW, COPIES = 2 * A_COPIES, HALF = COPIES / 2;
+    static constexpr int COPY_ROWS = 8, A_COPIES = BM / COPY_ROWS / NW, COPIES = 2 * A_COPIES;
+    static constexpr int TAILN = COPIES - HEADN;
+    static_assert(HEADN >= 1 && HEADN <= COPIES && 4 * TAILN <= MT * NT, "one memory instruction per MFMA slot");
     static_assert(LDS_BYTES <= 163840 && KSUB == 2 && BM == BN, "written for the 256x256x64 tile");
 
     using tile_t = wave::Tile<T, MT, NT>;
@@ -452,110 +460,96 @@ struct PersistentPipe {
         };
         auto read_slot = [](int r) constexpr { return 2 * r; };
         auto copy_slot = [](int c) constexpr { return 2 * c + 1; };
+        auto tail_slot = [](int c) constexpr { return 4 * c + 1; };
 
-        // One K step computing from slot `stage`.  Compile-time: HEAD (second half of the copies
-        // of the next step, from a1 / b1, into the other slot).  Run-time, for the last two steps
-        // of a tile only (RT): head, handover (a step follows: barrier + its first fragments),
-        // tail (first half of the copies of the step after next, from a2 / b2, into this slot),
-        // do_switch (load the copy offsets of tile switch_to between the two halves).
-        auto k_step = [&](auto rt_c, auto head_c, int stage, bool head, const char* a1, const char* b1,
-                          bool do_switch, const Source& switch_to, bool handover, bool tail, const char* a2,
-                          const char* b2) {
-            constexpr bool RT = decltype(rt_c)::value;
-            constexpr bool HEAD = decltype(head_c)::value;
+        // One K step computing from slot `stage`.  After the hand-over (wait, barrier, first
+        // fragments of the next step) this slot is free, and sub-step 1 issues the first TAILN
+        // copies of the step after next (from a2 / b2) into it; the remaining HEADN copies of
+        // that step follow in sub-step 0 of the next step (here: from a1 / b1 into the other
+        // slot).  "Next" steps past the end of a tile are the first steps of the following
+        // tile, so the loop never drains; switch_now loads that tile's copy offsets between
+        // the two halves.
+        auto k_step = [&](int stage, const char* a1, const char* b1, bool switch_now, const Source& to,
+                          const char* a2, const char* b2) {
             const int next = stage ^ 1;
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
 #pragma unroll
                 for (int r = 0; r < NR; ++r)
                     if (read_slot(r) == m) read(r, 1, stage, 1);
-                if (RT ? head : HEAD) {
 #pragma unroll
-                    for (int c = HALF; c < COPIES; ++c)
-                        if (copy_slot(c - HALF) == m) copy(c, a1, b1, next);
-                }
+                for (int c = TAILN; c < COPIES; ++c)
+                    if (copy_slot(c - TAILN) == m) copy(c, a1, b1, next);
                 mfma(m, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (RT && do_switch) set_offsets(switch_to);
-            if (!RT || handover) {
-                wait_counts<0, 0>();
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
+            if (switch_now) set_offsets(to);
+            wait_counts<0, 0>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+#pragma unroll
+                for (int r = 0; r < NR; ++r)
+                    if (read_slot(r) == m) read(r, 0, next, 0);
+#pragma unroll
+                for (int c = 0; c < TAILN; ++c)
+                    if (tail_slot(c) == m) copy(c, a2, b2, stage);
+                mfma(m, 1);
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int m = 0; m < NM; ++m) {
-#pragma unroll
-                    for (int r = 0; r < NR; ++r)
-                        if (read_slot(r) == m) read(r, 0, next, 0);
-                    if (!RT || tail) {
-#pragma unroll
-                        for (int c = 0; c < HALF; ++c)
-                            if (copy_slot(c) == m) copy(c, a2, b2, stage);
-                    }
-                    mfma(m, 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else {
-#pragma unroll
-                for (int m = 0; m < NM; ++m) mfma(m, 1);
             }
         };
-        using yes = std::integral_constant<bool, true>;
-        using no = std::integral_constant<bool, false>;
         constexpr int STEP = L::kRowBytes;  // bytes one K step advances in a row
+        // Keeps every accumulator block in the accumulation registers at the edges of the K
+        // loop, so that the register allocator does not rotate blocks through VGPRs inside it.
+        auto pin_acc = [&]() {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) asm volatile("" : "+a"(acc.acc[i][j]));
+        };
 
-        // -- first tile: steps 0 and 1 whole, then the first fragments
+        // -- before the first tile: step 0 whole, the first TAILN copies of step 1, the first fragments
         Source sc = first;
         int ksteps = first_ksteps;
         set_offsets(sc);
 #pragma unroll
         for (int c = 0; c < COPIES; ++c) copy(c, sc.a, sc.b, 0);
 #pragma unroll
-        for (int c = 0; c < COPIES; ++c) copy(c, sc.a + STEP, sc.b + STEP, 1);
-        wait_counts<COPIES, 0>();
+        for (int c = 0; c < TAILN; ++c) copy(c, sc.a + STEP, sc.b + STEP, 1);
+        wait_counts<TAILN, 0>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
 
         int stage = 0;
-        bool first_tile = true;
         for (;;) {
+            // Without a following tile the copies past the end re-read this tile's first two
+            // steps into slots nobody reads again: no branch around any copy.
             Source sn = sc;
-            int next_ksteps = 0;
+            int next_ksteps = ksteps;
             const bool has_next = peek(sn, next_ksteps);
             acc.clear();
-            int t = 0;
-            if (ksteps >= 3) {
-                // steps 0 .. ksteps-3: everything they copy belongs to this tile
-                if (first_tile) k_step(no{}, no{}, stage, false, sc.a + STEP, sc.b + STEP, false, sc, true, true, sc.a + 2 * STEP, sc.b + 2 * STEP);
-                else k_step(no{}, yes{}, stage, true, sc.a + STEP, sc.b + STEP, false, sc, true, true, sc.a + 2 * STEP, sc.b + 2 * STEP);
-                stage ^= 1;
-                for (t = 1; t + 3 <= ksteps; ++t) {
-                    const int64_t o = static_cast<int64_t>(t) * STEP;
-                    k_step(no{}, yes{}, stage, true, sc.a + o + STEP, sc.b + o + STEP, false, sc, true, true,
-                           sc.a + o + 2 * STEP, sc.b + o + 2 * STEP);
-                    stage ^= 1;
-                }
-            }
-            {   // step ksteps-2: second half of the last step; first half of the next tile's step 0
-                const int64_t o = static_cast<int64_t>(ksteps - 1) * STEP;
-                k_step(yes{}, no{}, stage, !(first_tile && t == 0), sc.a + o, sc.b + o, has_next, sn, true, has_next,
-                       sn.a, sn.b);
+            pin_acc();
+            for (int t = 0; t < ksteps; ++t) {
+                const int t1 = t + 1, t2 = t + 2;
+                const char* a1 = t1 < ksteps ? sc.a + static_cast<int64_t>(t1) * STEP : sn.a;
+                const char* b1 = t1 < ksteps ? sc.b + static_cast<int64_t>(t1) * STEP : sn.b;
+                const char* a2 = t2 < ksteps ? sc.a + static_cast<int64_t>(t2) * STEP : sn.a + static_cast<int64_t>(t2 - ksteps) * STEP;
+                const char* b2 = t2 < ksteps ? sc.b + static_cast<int64_t>(t2) * STEP : sn.b + static_cast<int64_t>(t2 - ksteps) * STEP;
+                k_step(stage, a1, b1, t2 == ksteps, sn, a2, b2);
                 stage ^= 1;
             }
-            // step ksteps-1: second half of the next tile's step 0, first half of its step 1
-            k_step(yes{}, no{}, stage, has_next, sn.a, sn.b, false, sn, has_next, has_next, sn.a + STEP, sn.b + STEP);
-            stage ^= 1;
-
+            pin_acc();
             finish(acc);
             if (!has_next) break;
             advance();
             sc = sn;
             ksteps = next_ksteps;
-            first_tile = false;
         }
+        wait_counts<0, 0>();  // the copies issued past the end of the last tile
     }
 };
 

@@ -119,7 +119,8 @@ def test_plans_for_the_five_workloads():
     assert p.workspace_bytes == p.split_k * 1024 * 1024 * 4
     assert p.workgroups == p.tiles_m * p.tiles_n * p.split_k
     p = _plan(P.make_desc(), 512, 512, 512, batch=256)
-    assert p.kernel == 2 and p.workgroups == p.tiles_m * p.tiles_n * 256 and p.split_k == 1
+    # many tiles with a short K loop: 256 persistent workgroups walk the 1024 tiles
+    assert p.kernel == 3 and p.workgroups == 256 and p.tiles_m * p.tiles_n == 4 and p.split_k == 1
 
 
 def test_plan_falls_back_to_staged_kernel():
