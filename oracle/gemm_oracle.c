@@ -126,3 +126,53 @@ int prism_oracle_gemm(int ab_dtype, int64_t M, int64_t N, int64_t K,
     }
     return 0;
 }
+
+/*
+ * The same definition for fp32 operands (the paper's sgemm, section 6.1:
+ * C <- alpha A B + beta C on float matrices).  A float converts to double
+ * exactly and the product of two floats (24-bit significands) is exact in
+ * double, so again the only rounding is the double accumulation.
+ * Arguments as prism_oracle_gemm, with A and B as floats.
+ */
+int prism_oracle_sgemm(int64_t M, int64_t N, int64_t K,
+                       const float* A, int64_t a_si, int64_t a_sk,
+                       const float* B, int64_t b_sk, int64_t b_sj,
+                       double alpha, double beta,
+                       const float* bias, const double* c_in,
+                       const int64_t* rows, int64_t n_rows,
+                       double* ref, double* mag)
+{
+    if (M < 0 || N < 0 || K < 0 || n_rows < 0)
+        return -1;
+    if (!rows && n_rows != M)
+        return -1;
+    if (beta != 0.0 && !c_in)
+        return -1;
+
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t r = 0; r < n_rows; ++r) {
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t i = rows ? rows[r] : r;
+            double s = 0.0, m = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = (double)A[i * a_si + k * a_sk] * (double)B[k * b_sk + j * b_sj];
+                s += p;
+                m += fabs(p);
+            }
+            double out = alpha * s;
+            double om = fabs(alpha) * m;
+            if (bias) {
+                out += (double)bias[j];
+                om += fabs((double)bias[j]);
+            }
+            if (beta != 0.0) {
+                double t = beta * c_in[i * N + j];
+                out += t;
+                om += fabs(t);
+            }
+            ref[r * N + j] = out;
+            mag[r * N + j] = om;
+        }
+    }
+    return 0;
+}

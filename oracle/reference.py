@@ -2,7 +2,8 @@
 
 Test infrastructure only: a plain fp64 triple loop for
 C <- alpha*A*B + bias + beta*C  (the paper's section 6.1 definition, with the
-16-bit operand types of its section 6.2 kernel).  This module marshals
+16-bit operand types of its section 6.2 kernel or the fp32 operands of its
+section 6.1 sgemm).  This module marshals
 arguments; the arithmetic is all in the C file.
 """
 from __future__ import annotations
@@ -42,6 +43,10 @@ def _load():
             ctypes.c_int, i64, i64, i64, vp, i64, i64, vp, i64, i64,
             dbl, dbl, vp, vp, vp, i64, vp, vp]
         lib.prism_oracle_gemm.restype = ctypes.c_int
+        lib.prism_oracle_sgemm.argtypes = [
+            i64, i64, i64, vp, i64, i64, vp, i64, i64,
+            dbl, dbl, vp, vp, vp, i64, vp, vp]
+        lib.prism_oracle_sgemm.restype = ctypes.c_int
         lib.prism_oracle_decode_bf16.argtypes = [ctypes.c_uint16]
         lib.prism_oracle_decode_bf16.restype = dbl
         lib.prism_oracle_decode_f16.argtypes = [ctypes.c_uint16]
@@ -73,12 +78,15 @@ def gemm_ref(A: np.ndarray, B: np.ndarray, *, ab_dtype: str, M: int, N: int, K: 
              alpha: float = 1.0, beta: float = 0.0,
              bias: Optional[np.ndarray] = None, c_in: Optional[np.ndarray] = None,
              rows: Optional[Sequence[int]] = None):
-    """One GEMM.  A, B: uint16 bit patterns as stored (any shape; read flat with
-    the given leading dimensions).  c_in: float64 [M, N] (already decoded).
+    """One GEMM.  A, B: uint16 bit patterns as stored, or float32 values when
+    ab_dtype is "f32" (any shape; read flat with the given leading dimensions).
+    c_in: float64 [M, N] (already decoded).
     Returns (ref, mag), float64 arrays of shape [len(rows) or M, N].
     """
-    A = np.ascontiguousarray(A, dtype=np.uint16).reshape(-1)
-    B = np.ascontiguousarray(B, dtype=np.uint16).reshape(-1)
+    store = np.float32 if ab_dtype == "f32" else np.uint16
+    assert np.asarray(A).dtype == store and np.asarray(B).dtype == store, "operands must be stored as " + str(store)
+    A = np.ascontiguousarray(A).reshape(-1)
+    B = np.ascontiguousarray(B).reshape(-1)
     if lda is None:
         lda = K if layout_a == "row" else M
     if ldb is None:
@@ -103,12 +111,14 @@ def gemm_ref(A: np.ndarray, B: np.ndarray, *, ab_dtype: str, M: int, N: int, K: 
         assert c_in.shape == (M, N)
     ref = np.empty((n_rows, N), dtype=np.float64)
     mag = np.empty((n_rows, N), dtype=np.float64)
-    rc = _load().prism_oracle_gemm(
-        _DTYPE_CODE[ab_dtype], M, N, K, _ptr(A), a_si, a_sk, _ptr(B), b_sk, b_sj,
-        float(alpha), float(beta), _ptr(bias), _ptr(c_in), _ptr(rows_arr), n_rows,
-        _ptr(ref), _ptr(mag))
+    tail = (_ptr(A), a_si, a_sk, _ptr(B), b_sk, b_sj, float(alpha), float(beta), _ptr(bias), _ptr(c_in),
+            _ptr(rows_arr), n_rows, _ptr(ref), _ptr(mag))
+    if ab_dtype == "f32":
+        rc = _load().prism_oracle_sgemm(M, N, K, *tail)
+    else:
+        rc = _load().prism_oracle_gemm(_DTYPE_CODE[ab_dtype], M, N, K, *tail)
     if rc != 0:
-        raise ValueError("prism_oracle_gemm rejected its arguments")
+        raise ValueError("the oracle rejected its arguments")
     return ref, mag
 
 
