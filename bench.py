@@ -17,13 +17,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_TFLOPS = 2516.6      # dense bf16 / fp16 matrix peak of MI355X (256 CU x 4096 FLOP/clk x 2.4 GHz)
+PEAK_MFMA_F32_TFLOPS = 157.3   # fp32 matrix peak (256 CU x 256 FLOP/clk x 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
 ESIZE = {"bf16": 2, "f16": 2, "f32": 4}
 
 
 def algorithmic_bytes(w) -> float:
     """Each operand read once, the result written once (plus the bias vector)."""
-    return w.batch * (w.M * w.K * 2 + w.K * w.N * 2 + w.M * w.N * ESIZE[w.c_dtype]) + (w.N * 4 if w.bias else 0)
+    es = ESIZE[w.ab_dtype]
+    c_bytes = w.M * w.N * ESIZE[w.c_dtype] * (2 if w.beta != 0.0 else 1)   # C is also read when beta != 0
+    return w.batch * (w.M * w.K * es + w.K * w.N * es + c_bytes) + (w.N * 4 if w.bias else 0)
 
 
 def source_digest() -> str:
@@ -88,13 +91,17 @@ def main() -> int:
     w = CONFIGS[args.workload]
     torch.cuda.set_device(0)
     inp = make_inputs(w)
-    A = torch.from_numpy(inp["A"].view(np.int16)).cuda()
-    B = torch.from_numpy(inp["B"].view(np.int16)).cuda()
+    A = torch.from_numpy(inp["A"] if w.ab_dtype == "f32" else inp["A"].view(np.int16)).cuda()
+    B = torch.from_numpy(inp["B"] if w.ab_dtype == "f32" else inp["B"].view(np.int16)).cuda()
     bias = None if inp["bias"] is None else torch.from_numpy(inp["bias"]).cuda()
     C = torch.empty(w.batch * w.M * w.N, dtype=torch.float32 if w.c_dtype == "f32" else torch.int16,
                     device="cuda")
+    C_in = None
+    if w.beta != 0.0:   # C <- alpha*A*B + beta*C is applied to the same C over and over; |beta| < 1 keeps it bounded
+        C_in = torch.from_numpy(inp["C_in"].ravel()).cuda()
+        C.copy_(C_in)
     desc = P.make_desc(ab_dtype=w.ab_dtype, c_dtype=w.c_dtype, layout_a=w.layout_a, layout_b=w.layout_b,
-                       alpha=w.alpha, bias=bias, split_k=w.split_k)
+                       alpha=w.alpha, beta=w.beta, bias=bias, split_k=w.split_k)
     s, ws_bytes = P.prism_gemm_workspace_size(desc, w.M, w.N, w.K, w.batch)
     assert s == 0
     ws = None
@@ -128,10 +135,11 @@ def main() -> int:
     tflops = w.flops / (ms_per_step * 1e-3) / 1e12
     launch_ms = dev_ms / args.steps                 # average duration of one launch of the path
     mfma_bound = w.name != "cfg5_batched_512"
+    peak_mfma = PEAK_MFMA_F32_TFLOPS if w.ab_dtype == "f32" else PEAK_MFMA_TFLOPS
     if mfma_bound:
         achieved = w.flops / (launch_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": None}
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak_mfma,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak_mfma, 4), "traffic": None}
     else:
         achieved = algorithmic_bytes(w) / (launch_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
@@ -143,16 +151,17 @@ def main() -> int:
         roofline["traffic"] = measured[0]
 
     out = {
-        "metric": "bf16 GEMM TFLOP/s and % of MI355X dense bf16 MFMA peak (1 GPU)",
+        "metric": ("fp32 GEMM TFLOP/s and % of MI355X fp32 MFMA peak (1 GPU)" if w.ab_dtype == "f32" else
+                   "bf16 GEMM TFLOP/s and % of MI355X dense bf16 MFMA peak (1 GPU)"),
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.ab_dtype == "bf16" else "f16", "data": "synthetic",
+        "dtype": w.ab_dtype, "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
                    "layout": f"A {w.layout_a}, B {w.layout_b}, C row", "c_dtype": w.c_dtype,
                    "tile": f"{plan.tile_m}x{plan.tile_n}x{plan.tile_k}", "waves": plan.waves,
                    "split_k": plan.split_k, "workgroups": plan.workgroups},
-        "pct_of_mfma_peak": round(100.0 * tflops / PEAK_MFMA_TFLOPS, 2),
+        "pct_of_mfma_peak": round(100.0 * tflops / peak_mfma, 2),
         "roofline": roofline,
     }
 
@@ -161,10 +170,16 @@ def main() -> int:
         from oracle import gemm_ref, oracle_threads, decode_output, check_against_oracle
         n_rows = min(args.cpu_rows, w.M)
         rows = np.unique(np.linspace(0, w.M - 1, n_rows).astype(np.int64))
+        c_in = None
+        if w.beta != 0.0:   # one more call from the stated initial C, so that the sample has a defined input
+            C.copy_(C_in)
+            step()
+            torch.cuda.synchronize()
+            c_in = inp["C_in"][0].astype(np.float64)
         t0 = time.perf_counter()
         ref, mag = gemm_ref(inp["A"][0], inp["B"][0], ab_dtype=w.ab_dtype, M=w.M, N=w.N, K=w.K,
-                            layout_a=w.layout_a, layout_b=w.layout_b, alpha=w.alpha,
-                            bias=inp["bias"], rows=rows)
+                            layout_a=w.layout_a, layout_b=w.layout_b, alpha=w.alpha, beta=w.beta,
+                            bias=inp["bias"], c_in=c_in, rows=rows)
         cpu_s = time.perf_counter() - t0
         got = C.cpu().numpy()
         got = got if w.c_dtype == "f32" else got.view(np.uint16)

@@ -5,12 +5,12 @@
  *
  *     C  <-  alpha * A * B  +  bias  +  beta * C
  *
- * with 16-bit floating-point operands (bf16 or fp16) and fp32 accumulation:
- * the matrix product the paper's evaluation is built on (section 6.1 defines
- * C <- alpha A B + beta C for its sgemm study; section 6.2 and the hgemm
- * kernel of the code appendix use bf16 operands, fp32 accumulators and a bf16
- * result).  The per-column bias and the split-K reduction are additions of
- * this library; the paper's kernels have neither.
+ * with 16-bit floating-point operands (bf16 or fp16) or fp32 operands, and
+ * fp32 accumulation: the matrix product the paper's evaluation is built on
+ * (section 6.1 defines C <- alpha A B + beta C for its fp32 sgemm study;
+ * section 6.2 and the hgemm kernel of the code appendix use bf16 operands,
+ * fp32 accumulators and a bf16 result).  The per-column bias and the split-K
+ * reduction are additions of this library; the paper's kernels have neither.
  *
  * All pointers named "device" are HIP device pointers owned by the caller; the
  * library never allocates or frees memory and keeps no mutable global state
@@ -39,7 +39,8 @@ extern "C" {
 typedef enum prism_status {
     PRISM_OK = 0,
     PRISM_ERR_INVALID_ARG = 1, /* null pointer, negative size, ld too small, overlap ... */
-    PRISM_ERR_UNSUPPORTED = 2, /* dtype / layout value outside the enums below        */
+    PRISM_ERR_UNSUPPORTED = 2, /* dtype / layout value outside the enums below, or
+                                  fp32 operands with a 16-bit result                  */
     PRISM_ERR_WORKSPACE = 3,   /* forced split_k > 1 but workspace missing / too small */
     PRISM_ERR_LAUNCH = 4       /* the HIP runtime refused the launch                   */
 } prism_status_t;
@@ -47,7 +48,7 @@ typedef enum prism_status {
 typedef enum prism_dtype {
     PRISM_DTYPE_BF16 = 0, /* 1-8-7 brain float, 2 bytes          */
     PRISM_DTYPE_F16 = 1,  /* IEEE binary16, 2 bytes              */
-    PRISM_DTYPE_F32 = 2   /* IEEE binary32, 4 bytes (C only)     */
+    PRISM_DTYPE_F32 = 2   /* IEEE binary32, 4 bytes              */
 } prism_dtype_t;
 
 typedef enum prism_layout {
@@ -61,7 +62,8 @@ typedef enum prism_layout {
  * during the call only.
  */
 typedef struct prism_gemm_desc {
-    int32_t ab_dtype;        /* prism_dtype_t: BF16 or F16, A and B alike             */
+    int32_t ab_dtype;        /* prism_dtype_t of A and B alike; F32 operands need an
+                                F32 result (else PRISM_ERR_UNSUPPORTED)                */
     int32_t c_dtype;         /* prism_dtype_t: BF16, F16 or F32                       */
     int32_t layout_a;        /* prism_layout_t                                        */
     int32_t layout_b;        /* prism_layout_t                                        */
@@ -107,10 +109,10 @@ typedef struct prism_gemm_plan {
  * hip_stream   a hipStream_t passed as void*; NULL is the default stream.
  *
  * M == 0 or N == 0: nothing is written, PRISM_OK.  K == 0: C <- bias + beta*C.
- * Any positive sizes, leading dimensions and alignments are accepted; operands
- * that are contiguous along K, 16-byte aligned and with K a multiple of 64 run
- * on the fast pipeline, everything else on a slower staged kernel with the
- * same arithmetic.  For a fixed problem, descriptor and GPU the result is
+ * Any positive sizes, leading dimensions and alignments are accepted; 16-bit
+ * operands that are contiguous along K, 16-byte aligned and with K a multiple
+ * of 64 run on the fast pipeline, everything else (fp32 operands included) on
+ * a staged kernel with the same arithmetic.  For a fixed problem, descriptor and GPU the result is
  * bit-for-bit reproducible: split-K partial sums are reduced in slice order.
  */
 PRISM_API prism_status_t prism_gemm(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,

@@ -128,4 +128,5 @@ def gemm_ref_workload(w, inputs: dict, *, batch_index: int = 0,
     return gemm_ref(inputs["A"][batch_index], inputs["B"][batch_index],
                     ab_dtype=w.ab_dtype, M=w.M, N=w.N, K=w.K,
                     layout_a=w.layout_a, layout_b=w.layout_b,
-                    alpha=w.alpha, bias=inputs.get("bias"), rows=rows)
+                    alpha=w.alpha, beta=w.beta, bias=inputs.get("bias"), rows=rows,
+                    c_in=None if w.beta == 0.0 else inputs["C_in"][batch_index].astype(np.float64))

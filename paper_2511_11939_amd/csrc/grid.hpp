@@ -15,15 +15,15 @@ enum : int { DT_BF16 = 0, DT_F16 = 1, DT_F32 = 2 };
 // Problem as the kernels see it: C is row-major (a column-major C has been
 // turned into the transposed problem on the host), strides are in elements.
 struct GemmParams {
-    const char* A;        // element (m, k) at A + 2*(m*a_sm + k*a_sk)
-    const char* B;        // element (k, n) at B + 2*(n*b_sn + k*b_sk)
+    const char* A;        // element (m, k) at A + esize*(m*a_sm + k*a_sk), esize 2 or 4
+    const char* B;        // element (k, n) at B + esize*(n*b_sn + k*b_sk)
     char* C;              // element (m, n) at C + esize*(m*ldc + n)
     const float* bias;    // or nullptr
     float* partial;       // split-K scratch [batch][split_k][M][N] fp32, or nullptr
     int64_t a_sm, a_sk, b_sn, b_sk, ldc;
     int64_t batch_a, batch_b, batch_c;
     int M, N, K;
-    int batch, split_k, k_slice;   // k_slice: K extent of one slice, a multiple of 64
+    int batch, split_k, k_slice;   // k_slice: K extent of one slice, whole K steps
     int tiles_m, tiles_n;
     float alpha, beta;
     int c_dtype;          // DT_*

@@ -15,7 +15,7 @@ namespace {
 using prism::GemmParams;
 
 constexpr int kComputeUnits = 256;
-constexpr int kPersistentMaxSteps = 16;  // longest K loop (in steps of 64) the persistent kernel is chosen for
+constexpr int kPersistentMaxSteps = 16;  // longest K loop (in K steps) the persistent kernel is chosen for
 constexpr int kMaxSplit = 64;
 constexpr int64_t kIntMax = 2147483647;
 
@@ -27,7 +27,7 @@ struct Problem {
     int total_units;  // (tile, unit) pairs the persistent kernel walks
 };
 
-bool valid_dtype_ab(int v) { return v == PRISM_DTYPE_BF16 || v == PRISM_DTYPE_F16; }
+bool valid_dtype_ab(int v) { return v == PRISM_DTYPE_BF16 || v == PRISM_DTYPE_F16 || v == PRISM_DTYPE_F32; }
 bool valid_dtype_c(int v) { return v == PRISM_DTYPE_BF16 || v == PRISM_DTYPE_F16 || v == PRISM_DTYPE_F32; }
 bool valid_layout(int v) { return v == PRISM_ROW_MAJOR || v == PRISM_COL_MAJOR; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -66,6 +66,7 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     if (!valid_dtype_ab(d->ab_dtype) || !valid_dtype_c(d->c_dtype) || !valid_layout(d->layout_a) ||
         !valid_layout(d->layout_b) || !valid_layout(d->layout_c))
         return PRISM_ERR_UNSUPPORTED;
+    if (d->ab_dtype == PRISM_DTYPE_F32 && d->c_dtype != PRISM_DTYPE_F32) return PRISM_ERR_UNSUPPORTED;
     if (d->reserved != 0) return PRISM_ERR_INVALID_ARG;
     if (M < 0 || N < 0 || K < 0 || batch < 0 || d->split_k < 0) return PRISM_ERR_INVALID_ARG;
     if (M > kIntMax || N > kIntMax || K > kIntMax - 64 || batch > kIntMax) return PRISM_ERR_INVALID_ARG;
@@ -84,6 +85,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     const int64_t c_span = span(d->layout_c, M, N, ldc);
     const int64_t a_span = span(d->layout_a, M, K, lda), b_span = span(d->layout_b, K, N, ldb);
     const int c_esize = d->c_dtype == PRISM_DTYPE_F32 ? 4 : 2;
+    const int ab_esize = d->ab_dtype == PRISM_DTYPE_F32 ? 4 : 2;
+    const int epc = 16 / ab_esize;  // operand elements per 16-byte chunk
     if (need_pointers) {
         if (!C || (K > 0 && (!A || !B))) return PRISM_ERR_INVALID_ARG;
     }
@@ -95,8 +98,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         // C must not share memory with A or B (checked over the whole batch extent)
         const int64_t nb = batch - 1;
         const int64_t c_bytes = (nb * strideC + c_span) * c_esize;
-        if (overlaps(C, c_bytes, A, (nb * strideA + a_span) * 2) ||
-            overlaps(C, c_bytes, B, (nb * strideB + b_span) * 2))
+        if (overlaps(C, c_bytes, A, (nb * strideA + a_span) * ab_esize) ||
+            overlaps(C, c_bytes, B, (nb * strideB + b_span) * ab_esize))
             return PRISM_ERR_INVALID_ARG;
     }
 
@@ -129,8 +132,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
 
     // ---- alignment facts
     const bool a_kfast = p.a_sk == 1, b_kfast = p.b_sk == 1;
-    p.a_vec = a_kfast && aligned(p.A, 16) && p.a_sm % 8 == 0 && (p.batch == 1 || p.batch_a % 8 == 0);
-    p.b_vec = b_kfast && aligned(p.B, 16) && p.b_sn % 8 == 0 && (p.batch == 1 || p.batch_b % 8 == 0);
+    p.a_vec = a_kfast && aligned(p.A, 16) && p.a_sm % epc == 0 && (p.batch == 1 || p.batch_a % epc == 0);
+    p.b_vec = b_kfast && aligned(p.B, 16) && p.b_sn % epc == 0 && (p.batch == 1 || p.batch_b % epc == 0);
     const size_t c_align = 4 * static_cast<size_t>(c_esize);
     p.c_vec = aligned(p.C, c_align) && p.ldc % 4 == 0 && (p.batch == 1 || p.batch_c % 4 == 0) &&
               (!p.bias || p.bias_along_m || aligned(p.bias, 4));
@@ -146,8 +149,9 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     }
 
     // ---- kernel and tile shape
-    const int64_t ksteps = ceil_div(K, 64);
-    const bool pipe_ok = p.a_vec && p.b_vec && K % 64 == 0 && p.a_sm < (int64_t{1} << 21) &&
+    const int64_t step_k = 128 / ab_esize;  // a K step is 128 bytes of every operand row
+    const int64_t ksteps = ceil_div(K, step_k);
+    const bool pipe_ok = ab_esize == 2 && p.a_vec && p.b_vec && K % 64 == 0 && p.a_sm < (int64_t{1} << 21) &&
                          p.b_sn < (int64_t{1} << 21);
     int tile_m = prism::kStagedTileM, tile_n = prism::kStagedTileN, waves = prism::kStagedWaves;
     plan.kernel = 1;
@@ -189,13 +193,13 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         split = 1; slice_steps = ksteps; ws_need = 0;  // library's own choice: fall back quietly
     }
     p.split_k = static_cast<int>(split);
-    p.k_slice = static_cast<int>(slice_steps * 64);
+    p.k_slice = static_cast<int>(slice_steps * step_k);
     p.partial = split > 1 ? static_cast<float*>(d->workspace) : nullptr;
     p.tiles_m = static_cast<int>(tiles_m);
     p.tiles_n = static_cast<int>(tiles_n);
 
     plan.tile_m = tile_m; plan.tile_n = tile_n; plan.waves = waves;
-    plan.tile_k = plan.kernel >= 2 ? prism::kPipeConfigs[out->pipe_config].tile_k : 64;
+    plan.tile_k = plan.kernel >= 2 ? prism::kPipeConfigs[out->pipe_config].tile_k : static_cast<int32_t>(step_k);
     plan.split_k = static_cast<int32_t>(split);
     plan.tiles_m = tiles_m; plan.tiles_n = tiles_n;
     plan.workgroups = units * split;

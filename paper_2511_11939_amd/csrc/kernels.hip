@@ -175,8 +175,8 @@ __global__ __launch_bounds__(256) void gemm_staged(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Placement q = place<S::BM, S::BN>(p, blockIdx.x);
 
-    const char* a_tile = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm);
-    const char* b_tile = p.B + 2 * (q.batch * p.batch_b + q.n0 * p.b_sn);
+    const char* a_tile = p.A + S::ES * (q.batch * p.batch_a + q.m0 * p.a_sm);
+    const char* b_tile = p.B + S::ES * (q.batch * p.batch_b + q.n0 * p.b_sn);
     const int a_rows = p.M - q.m0 < S::BM ? p.M - q.m0 : S::BM;
     const int b_rows = p.N - q.n0 < S::BN ? p.N - q.n0 : S::BN;
 
@@ -258,8 +258,10 @@ hipError_t launch_staged(int ab_dtype, const GemmParams& p, int workgroups, hipS
 {
     if (ab_dtype == DT_BF16)
         hipLaunchKernelGGL(gemm_staged<bf16_t>, dim3(workgroups), dim3(256), 0, stream, p);
-    else
+    else if (ab_dtype == DT_F16)
         hipLaunchKernelGGL(gemm_staged<f16_t>, dim3(workgroups), dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(gemm_staged<f32_t>, dim3(workgroups), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -21,10 +21,14 @@ using u32x2 = __attribute__((ext_vector_type(2))) uint32_t;
 
 struct bf16_t {};  // operand tags
 struct f16_t {};
+struct f32_t {};
 
+// A fragment is one lane's 16 bytes of an operand row: 8 consecutive k of a 16-bit type,
+// 4 consecutive k of fp32.
 template <typename T> struct Frag;
-template <> struct Frag<bf16_t> { using type = bf16x8; };
-template <> struct Frag<f16_t> { using type = f16x8; };
+template <> struct Frag<bf16_t> { using type = bf16x8; static constexpr int kElemBytes = 2; };
+template <> struct Frag<f16_t> { using type = f16x8; static constexpr int kElemBytes = 2; };
+template <> struct Frag<f32_t> { using type = f32x4; static constexpr int kElemBytes = 4; };
 
 namespace lane {
 

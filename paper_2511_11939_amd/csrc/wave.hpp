@@ -12,19 +12,29 @@
 namespace prism {
 namespace wave {
 
-// D[i][j] += sum_k R[i][k] * C[j][k]  for a 16 x 16 x 32 block.
+// D[i][j] += sum_k R[i][k] * C[j][k]  for a 16 x 16 block and the k range of one fragment
+// pair (32 k of a 16-bit type, 16 k of fp32).
 // `r` / `c`: each lane's 8 consecutive k of row (lane%16), k-quarter (lane/16).
 // Result layout: see lane::acc_row / lane::acc_col.  Of the two bf16 shapes of
 // gfx950 this one needs less energy per multiply-add (a quarter of the
 // accumulator registers are read and written per instruction), and on this
 // power-limited part that shows directly as a higher sustained clock.
-__device__ __forceinline__ f32x4 mfma_16x16x32(bf16x8 r, bf16x8 c, f32x4 acc)
+__device__ __forceinline__ f32x4 mfma_block(bf16x8 r, bf16x8 c, f32x4 acc)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc, 0, 0, 0);
 }
-__device__ __forceinline__ f32x4 mfma_16x16x32(f16x8 r, f16x8 c, f32x4 acc)
+__device__ __forceinline__ f32x4 mfma_block(f16x8 r, f16x8 c, f32x4 acc)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(r, c, acc, 0, 0, 0);
+}
+
+// fp32 operands: a fragment holds 4 consecutive k per lane; MFMA e of the four takes element
+// e of both fragments, so lane group g (lane/16) contributes k = 4g + e to it.
+__device__ __forceinline__ f32x4 mfma_block(f32x4 r, f32x4 c, f32x4 acc)
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(r[e], c[e], acc, 0, 0, 0);
+    return acc;
 }
 
 // Register-blocked wave tile: MT x NT accumulator blocks of 16 x 16.  The B
@@ -49,7 +59,7 @@ struct Tile {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < NT; ++j) acc[i][j] = mfma_16x16x32(b[j], a[i], acc[i][j]);
+            for (int j = 0; j < NT; ++j) acc[i][j] = mfma_block(b[j], a[i], acc[i][j]);
     }
 };
 

@@ -232,7 +232,7 @@ struct Pipeline {
         };
         auto mfma = [&](int m, int buf) {
             const int i = m / NT, j = m % NT;
-            acc.acc[i][j] = wave::mfma_16x16x32(fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            acc.acc[i][j] = wave::mfma_block(fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
 
         // -- prologue: fill the slots, wait for step 0, fetch its first fragments
@@ -456,7 +456,7 @@ struct PersistentPipe {
         };
         auto mfma = [&](int m, int buf) {
             const int i = m / NT, j = m % NT;
-            acc.acc[i][j] = wave::mfma_16x16x32(fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            acc.acc[i][j] = wave::mfma_block(fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
         auto read_slot = [](int r) constexpr { return 2 * r; };
         auto copy_slot = [](int c) constexpr { return 2 * c + 1; };
@@ -554,15 +554,20 @@ struct PersistentPipe {
 };
 
 // ------------------------------------------------------------------------------------
-// Staged main loop: any element strides and alignments; operands pass through
-// registers, are zero-filled outside the matrix and written to one LDS slot.
+// Staged main loop: any element strides and alignments, 16-bit or fp32 operands.  The
+// operands of a K step pass through registers, are zero-filled outside the matrix and
+// written to one LDS slot; the loads of step t+1 are in flight while step t computes.
+// A K step is 128 bytes of every operand row (64 elements of a 16-bit type, 32 of fp32).
+// This is the paper's sgemm structure (section 6.1: block tile staged in shared memory,
+// then warp- and thread-level tiles), with the thread-level tile replaced by MFMA blocks.
 // ------------------------------------------------------------------------------------
 template <typename T>
 struct Staged {
-    using L = lane::TileLayout<64>;
-    static constexpr int BM = 128, BN = 128, BK = 64, NW = 4, THREADS = 256;
+    using L = lane::TileLayout<64>;  // rows of 128 bytes
+    static constexpr int ES = Frag<T>::kElemBytes, EPC = lane::kChunkBytes / ES;  // elements per chunk
+    static constexpr int BM = 128, BN = 128, BK = L::kRowBytes / ES, NW = 4, THREADS = 256;
     static constexpr int WTM = 64, WTN = 64, MT = WTM / lane::kBlock, NT = WTN / lane::kBlock;
-    static constexpr int KSUB = BK / lane::kBlockK;
+    static constexpr int KSUB = L::kChunksPerRow / 4;  // a fragment read covers 4 chunks of a row
     static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes;
     static constexpr int DRAIN_BYTES = NW * drain_patch_bytes(NT);
     static constexpr int LDS_BYTES = A_BYTES + B_BYTES > DRAIN_BYTES ? A_BYTES + B_BYTES : DRAIN_BYTES;
@@ -570,11 +575,15 @@ struct Staged {
 
     using tile_t = wave::Tile<T, MT, NT>;
     using frag_t = typename Frag<T>::type;
+    using elem_t = typename std::conditional<ES == 2, uint16_t, uint32_t>::type;
 
-    // One thread's share of a 128 x 64 operand tile as CHUNKS 16-byte chunks.
+    // One thread's share of a 128-row operand tile as CHUNKS 16-byte chunks.
     // base: element (row 0 of the tile, k 0 of the matrix); s_row / s_k: element
     // strides; rows: rows that exist; k0: first k of this step; k_end: end of
     // the slice.  vec: rows are K-contiguous and every chunk is 16-byte aligned.
+    // With K-contiguous rows consecutive threads take consecutive chunks of a row,
+    // otherwise consecutive rows of one chunk, so that either way they read
+    // neighbouring addresses.
     __device__ __forceinline__ static void gather(u32x4 (&regs)[CHUNKS], const char* base, int64_t s_row, int64_t s_k,
                                   int rows, int k0, int k_end, bool vec, int tid)
     {
@@ -584,18 +593,21 @@ struct Staged {
             const int q = tid + THREADS * i;
             const int row = k_fast ? q / L::kChunksPerRow : q % BM;
             const int c = k_fast ? q % L::kChunksPerRow : q / BM;
-            const int k = k0 + 8 * c;
+            const int k = k0 + EPC * c;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (row < rows && k < k_end) {
-                const char* src = base + 2 * (row * s_row + k * s_k);
-                if (vec && k + 8 <= k_end) {
+                const char* src = base + ES * (row * s_row + k * s_k);
+                if (vec && k + EPC <= k_end) {
                     v = *reinterpret_cast<const u32x4*>(src);
                 } else {
-                    uint32_t h[8];
+                    uint32_t h[EPC];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        h[e] = (k + e < k_end) ? *reinterpret_cast<const uint16_t*>(src + 2 * e * s_k) : 0u;
-                    v = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                    for (int e = 0; e < EPC; ++e)
+                        h[e] = (k + e < k_end) ? *reinterpret_cast<const elem_t*>(src + ES * e * s_k) : 0u;
+                    if constexpr (ES == 2)
+                        v = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                    else
+                        v = u32x4{h[0], h[1], h[2], h[3]};
                 }
             }
             regs[i] = v;
@@ -620,18 +632,22 @@ struct Staged {
         const int tid = wave * 64 + lane;
         const int wave_m = wave >> 1, wave_n = wave & 1;
         u32x4 ra[CHUNKS], rb[CHUNKS];
+        gather(ra, a_tile, a_sm, a_sk, a_rows, k_begin, k_end, a_vec, tid);
+        gather(rb, b_tile, b_sn, b_sk, b_rows, k_begin, k_end, b_vec, tid);
         for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-            gather(ra, a_tile, a_sm, a_sk, a_rows, k0, k_end, a_vec, tid);
-            gather(rb, b_tile, b_sn, b_sk, b_rows, k0, k_end, b_vec, tid);
             __syncthreads();  // the previous step's fragment reads are finished
             commit(ra, lds, a_sk == 1, tid);
             commit(rb, lds + A_BYTES, b_sk == 1, tid);
             __syncthreads();
+            if (k0 + BK < k_end) {  // next step's operands travel while this one computes
+                gather(ra, a_tile, a_sm, a_sk, a_rows, k0 + BK, k_end, a_vec, tid);
+                gather(rb, b_tile, b_sn, b_sk, b_rows, k0 + BK, k_end, b_vec, tid);
+            }
 #pragma unroll
             for (int ks = 0; ks < KSUB; ++ks) {
                 frag_t fa[MT], fb[NT];
-                wave::load_fragments<T, BK, MT>(fa, lds, wave_m * WTM, ks, lane);
-                wave::load_fragments<T, BK, NT>(fb, lds + A_BYTES, wave_n * WTN, ks, lane);
+                wave::load_fragments<T, 64, MT>(fa, lds, wave_m * WTM, ks, lane);
+                wave::load_fragments<T, 64, NT>(fb, lds + A_BYTES, wave_n * WTN, ks, lane);
                 acc.mma(fa, fb);
             }
         }

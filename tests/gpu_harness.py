@@ -13,8 +13,9 @@ ESIZE = {"bf16": 2, "f16": 2, "f32": 4}
 
 
 def to_dev(bits: np.ndarray) -> torch.Tensor:
-    """uint16 bit patterns -> device int16 tensor with the same bytes."""
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    """uint16 bit patterns -> device int16 tensor with the same bytes; float32 stays float32."""
+    bits = np.ascontiguousarray(bits)
+    return torch.from_numpy(bits if bits.dtype == np.float32 else bits.view(np.int16)).cuda()
 
 
 def alloc_c(n_elems: int, c_dtype: str, fill=None) -> torch.Tensor:
@@ -47,8 +48,11 @@ def run_workload(w: GemmWorkload, inputs: dict, *, c_dtype=None, split_k=None, s
     A, B = to_dev(inputs["A"]), to_dev(inputs["B"])
     bias = None if inputs.get("bias") is None else torch.from_numpy(inputs["bias"]).cuda()
     C = alloc_c(w.batch * w.M * w.N, c_dtype)
+    if w.beta != 0.0:
+        assert c_dtype == "f32", "workloads with beta keep C in fp32"
+        C.copy_(torch.from_numpy(inputs["C_in"].ravel()))
     desc = P.make_desc(ab_dtype=w.ab_dtype, c_dtype=c_dtype, layout_a=w.layout_a, layout_b=w.layout_b,
-                       alpha=w.alpha, bias=bias, split_k=w.split_k if split_k is None else split_k)
+                       alpha=w.alpha, beta=w.beta, bias=bias, split_k=w.split_k if split_k is None else split_k)
     ws = workspace_for(desc, w.M, w.N, w.K, w.batch)
     s, plan = P.prism_gemm_plan(desc, w.M, w.N, w.K, A, w.lda(), w.M * w.K, B, w.ldb(), w.K * w.N,
                                 C, w.N, w.M * w.N, w.batch)
@@ -67,7 +71,8 @@ def assert_matches_oracle(w: GemmWorkload, inputs: dict, c_stored: np.ndarray, *
     c_dtype = c_dtype or w.c_dtype
     ref, mag = gemm_ref(inputs["A"][batch_index], inputs["B"][batch_index], ab_dtype=w.ab_dtype,
                         M=w.M, N=w.N, K=w.K, layout_a=w.layout_a, layout_b=w.layout_b,
-                        alpha=w.alpha, bias=inputs.get("bias"), rows=rows)
+                        alpha=w.alpha, beta=w.beta, bias=inputs.get("bias"), rows=rows,
+                        c_in=None if w.beta == 0.0 else inputs["C_in"][batch_index].astype(np.float64))
     got = c_stored[batch_index]
     if rows is not None:
         got = got[np.asarray(rows)]

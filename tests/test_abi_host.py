@@ -181,3 +181,17 @@ def test_scheduler_gives_each_die_a_compact_block():
             rows.add(a)
             cols.add(b)
         assert len(rows) * len(cols) <= 64 and len(rows) + len(cols) <= 12
+
+
+def test_fp32_operands_need_an_fp32_result():
+    FAKE_A, FAKE_B, FAKE_C = FAKE, FAKE + (1 << 30), FAKE + (2 << 30)
+    for cd in ("bf16", "f16"):
+        d = P.make_desc(ab_dtype="f32", c_dtype=cd)
+        assert P.prism_gemm(d, 64, 64, 64, FAKE_A, 64, FAKE_B, 64, FAKE_C, 64, None) == S.UNSUPPORTED
+    d = P.make_desc(ab_dtype="f32", c_dtype="f32", layout_b="row")
+    s, plan = P.prism_gemm_plan(d, 4096, 4096, 4096, None, 4096, 0, None, 4096, 0, None, 4096, 0, 1)
+    assert s == S.OK and plan.kernel == 1 and plan.tile_k == 32 and plan.workgroups == 32 * 32
+    # overlap is measured in bytes of the real element size
+    assert P.prism_gemm(d, 64, 64, 64, FAKE_A, 64, FAKE_B, 64, FAKE_A + 64 * 64 * 4 - 4, 64, None) == S.INVALID_ARG
+    s, _ = P.prism_gemm_plan(d, 64, 64, 64, FAKE_A, 64, 0, FAKE_B, 64, 0, FAKE_A + 64 * 64 * 4, 64, 0, 1)
+    assert s == S.OK

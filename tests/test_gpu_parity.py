@@ -19,7 +19,7 @@ from gpu_harness import (run_workload, assert_matches_oracle, tile_probe_rows, t
 
 pytestmark = pytest.mark.gpu
 
-ENC = {"bf16": to_bf16_bits, "f16": to_f16_bits}
+ENC = {"bf16": to_bf16_bits, "f16": to_f16_bits, "f32": lambda v: np.asarray(v, dtype=np.float32)}
 
 
 def _exact_int_product(w, inputs, batch_index=0):
@@ -205,14 +205,15 @@ def _general_case(M, N, K, *, ab="bf16", cd="f32", la="row", lb="col", lc="row",
         t[offset:] = src
         return t
 
-    dA, dB = dev(A), dev(B)
+    dA, dB = dev(A, dtype16=(ab != "f32")), dev(B, dtype16=(ab != "f32"))
     dC = dev(C0, dtype16=(cd != "f32"))
     dbias = None if bias_v is None else torch.from_numpy(bias_v).cuda()
     desc = P.make_desc(ab_dtype=ab, c_dtype=cd, layout_a=la, layout_b=lb, layout_c=lc,
                        alpha=alpha, beta=beta, bias=dbias, split_k=split_k)
     ws = workspace_for(desc, M, N, K, batch)
     es_c = 4 if cd == "f32" else 2
-    P.gemm(dA.data_ptr() + 2 * offset, dB.data_ptr() + 2 * offset, dC.data_ptr() + es_c * offset,
+    es_ab = 4 if ab == "f32" else 2
+    P.gemm(dA.data_ptr() + es_ab * offset, dB.data_ptr() + es_ab * offset, dC.data_ptr() + es_c * offset,
            M=M, N=N, K=K, desc=desc, lda=lda, ldb=ldb, ldc=ldc, batch=batch,
            strideA=strideA, strideB=strideB, strideC=strideC)
     torch.cuda.synchronize()
@@ -282,6 +283,47 @@ def test_persistent_kernel_forced(M, N, K, batch, split, monkeypatch):
     assert s == 0 and plan.kernel == 3 and plan.workgroups <= 256
     _general_case(M, N, K, ints=True, batch=batch, split_k=split)
     _general_case(M, N, K, ab="f16", cd="bf16", bias=True, alpha=-1.25, batch=batch, split_k=split)
+
+
+# ---- fp32 operands: the sgemm of the paper's section 6.1 ------------------------------------
+
+@pytest.mark.parametrize("la,lb,lc", [("row", "row", "row"), ("row", "col", "row"), ("col", "row", "row"),
+                                      ("col", "col", "col"), ("row", "row", "col")])
+def test_sgemm_layouts_alpha_beta(la, lb, lc):
+    _general_case(130, 71, 100, ab="f32", la=la, lb=lb, lc=lc, pad=(3, 5, 2), alpha=0.5, beta=-1.5, bias=True)
+    _general_case(256, 384, 96, ab="f32", la=la, lb=lb, lc=lc, ints=True)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 5, 3), (33, 129, 31), (128, 128, 32), (255, 257, 65), (300, 200, 1000)])
+def test_sgemm_odd_shapes(M, N, K):
+    _general_case(M, N, K, ab="f32", la="row", lb="row", ints=True)
+    _general_case(M, N, K, ab="f32", la="row", lb="row", alpha=-2.0, beta=0.25)
+
+
+def test_sgemm_split_batch_unaligned_and_degenerate():
+    _general_case(128, 128, 2048, ab="f32", lb="row", split_k=4, ints=True)
+    _general_case(100, 60, 1000, ab="f32", lb="row", split_k=3, bias=True, beta=0.5)
+    _general_case(96, 80, 64, ab="f32", lb="row", batch=5, pad=(4, 4, 4))
+    _general_case(96, 80, 128, ab="f32", lb="row", pad=(1, 1, 1), offset=1, bias=True)
+    _general_case(64, 48, 0, ab="f32", lb="row", bias=True, beta=2.0)
+    _general_case(0, 48, 16, ab="f32", lb="row")
+
+
+def test_sgemm_4096_workload_sampled_rows():
+    """The benchmark's fp32 workload at full size: rows from every workgroup tile and wave."""
+    w = CONFIGS["sgemm_4096_rowrow"]
+    inp = make_inputs(w)
+    c, plan = run_workload(w, inp)
+    assert plan["kernel"] == 1 and plan["tile_k"] == 32
+    rows = tile_probe_rows(w.M, plan["tile_m"], per_tile=(0, 15, 16, 63, 64, 127))
+    assert_matches_oracle(w, inp, c, rows=rows)
+    c2, _ = run_workload(w, inp)
+    assert (c == c2).all()                     # run-to-run bit-identical
+
+
+def test_sgemm_square_1024_every_entry():
+    """Row-major A, B and C as in the paper's sgemm study, several tiles in each direction."""
+    _general_case(1024, 1024, 1024, ab="f32", la="row", lb="row", alpha=1.5, beta=0.5, seed=3)
 
 
 def test_unaligned_pointers_and_odd_ld():

@@ -1,4 +1,4 @@
-"""The five synthetic GEMM workloads and how their operands are laid out.
+"""The synthetic GEMM workloads and how their operands are laid out.
 
 Storage convention (shared by every consumer): A is the logical M x K matrix,
 B the logical K x N matrix, C the logical M x N matrix.  "row" means the last
@@ -22,7 +22,7 @@ class GemmWorkload:
     N: int
     K: int
     batch: int = 1
-    ab_dtype: str = "bf16"          # "bf16" | "f16"
+    ab_dtype: str = "bf16"          # "bf16" | "f16" | "f32"
     c_dtype: str = "f32"            # "bf16" | "f16" | "f32"
     layout_a: str = "row"
     layout_b: str = "col"
@@ -30,6 +30,7 @@ class GemmWorkload:
     dist_b: Tuple = ("normal", 1.0)
     bias: bool = False
     alpha: float = 1.0
+    beta: float = 0.0               # != 0: C holds N(0, 1) values (tensor 3) before the call
     split_k: int = 0                # 0 = library decides, 1 = off, n = forced
     seed: int = 0x5EED0000
 
@@ -69,6 +70,11 @@ CONFIGS = {
     "cfg5_batched_512": GemmWorkload(
         "cfg5_batched_512", 512, 512, 512, batch=256, ab_dtype="bf16", c_dtype="bf16",
         seed=0x5EED0005),
+    # fp32 sgemm, every matrix row-major, both scalars in use
+    "sgemm_4096_rowrow": GemmWorkload(
+        "sgemm_4096_rowrow", 4096, 4096, 4096, ab_dtype="f32", c_dtype="f32",
+        layout_a="row", layout_b="row", dist_a=("uniform",), dist_b=("uniform",),
+        alpha=1.5, beta=0.5, seed=0x5EED0006),
 }
 
 
@@ -94,11 +100,13 @@ def _store(x: np.ndarray, batch: int, rows: int, cols: int, layout: str) -> np.n
 
 
 def make_inputs(w: GemmWorkload) -> dict:
-    """Returns {"A": uint16[batch, ...], "B": uint16[batch, ...], "bias": float32[N] | None}.
+    """Returns {"A": [batch, ...], "B": [batch, ...], "bias": float32[N] | None,
+    "C_in": float32[batch, M, N] | None}.
 
     A is stored [batch, M, K] (row) or [batch, K, M] (col); B is stored
-    [batch, K, N] (row) or [batch, N, K] (col).  Values are 16-bit patterns of
-    `w.ab_dtype`, rounded once from float32 draws.
+    [batch, K, N] (row) or [batch, N, K] (col).  Values are uint16 bit patterns of
+    `w.ab_dtype`, rounded once from float32 draws, or the float32 draws themselves
+    for fp32 operands.  C_in (only for beta != 0) is what C holds before the call.
     """
     a = _draw(w.dist_a, w.seed, 0, w.batch * w.M * w.K)
     b = _draw(w.dist_b, w.seed, 1, w.batch * w.K * w.N)
@@ -107,4 +115,7 @@ def make_inputs(w: GemmWorkload) -> dict:
     bias: Optional[np.ndarray] = None
     if w.bias:
         bias = g.normal(w.seed, 2, w.N, 1.0)
-    return {"A": A, "B": B, "bias": bias}
+    c_in = None
+    if w.beta != 0.0:
+        c_in = g.normal(w.seed, 3, w.batch * w.M * w.N, 1.0).reshape(w.batch, w.M, w.N)
+    return {"A": A, "B": B, "bias": bias, "C_in": c_in}

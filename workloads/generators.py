@@ -85,4 +85,6 @@ def encode(x: np.ndarray, dtype: str) -> np.ndarray:
         return to_bf16_bits(x)
     if dtype == "f16":
         return to_f16_bits(x)
+    if dtype == "f32":
+        return np.asarray(x, dtype=np.float32)
     raise ValueError(dtype)
