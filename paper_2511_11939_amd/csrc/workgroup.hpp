@@ -614,14 +614,60 @@ struct Staged {
         }
     }
 
-    __device__ __forceinline__ static void commit(const u32x4 (&regs)[CHUNKS], char* tile, bool k_fast, int tid)
+    // Where one thread's chunks of a whole K step come from, for an operand whose chunks can be
+    // fetched without looking at k: byte offsets from the step's first element (rows beyond the
+    // matrix re-read the last row and are zeroed in commit).  Valid when the operand is
+    // K-contiguous with aligned chunks, or contiguous along its rows.
+    struct Regular {
+        uint32_t off[CHUNKS];
+        bool inside[CHUNKS];
+    };
+    __device__ __forceinline__ static Regular regular(int64_t s_row, int64_t s_k, int rows, int tid)
+    {
+        Regular r;
+        const bool k_fast = s_k == 1;
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int q = tid + THREADS * i;
+            const int row = k_fast ? q / L::kChunksPerRow : q % BM;
+            const int c = k_fast ? q % L::kChunksPerRow : q / BM;
+            r.inside[i] = row < rows;
+            r.off[i] = static_cast<uint32_t>(ES * ((row < rows ? row : rows - 1) * s_row + EPC * c * s_k));
+        }
+        return r;
+    }
+    // All chunks of a K step that lies wholly inside the slice; step0 points at (row 0, first k
+    // of the step).  No address arithmetic per lane: uniform base plus the fixed offsets.
+    __device__ __forceinline__ static void gather_regular(u32x4 (&regs)[CHUNKS], const char* step0, int64_t s_k,
+                                                          const Regular& r)
+    {
+        if (s_k == 1) {
+#pragma unroll
+            for (int i = 0; i < CHUNKS; ++i) regs[i] = *reinterpret_cast<const u32x4*>(step0 + r.off[i]);
+        } else {
+            const int64_t pitch = ES * s_k;
+#pragma unroll
+            for (int i = 0; i < CHUNKS; ++i) {
+                uint32_t h[EPC];
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) h[e] = *reinterpret_cast<const elem_t*>(step0 + e * pitch + r.off[i]);
+                if constexpr (ES == 2)
+                    regs[i] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                else
+                    regs[i] = u32x4{h[0], h[1], h[2], h[3]};
+            }
+        }
+    }
+
+    __device__ __forceinline__ static void commit(const u32x4 (&regs)[CHUNKS], const bool (&inside)[CHUNKS], char* tile,
+                                                  bool k_fast, int tid)
     {
 #pragma unroll
         for (int i = 0; i < CHUNKS; ++i) {
             const int q = tid + THREADS * i;
             const int row = k_fast ? q / L::kChunksPerRow : q % BM;
             const int c = k_fast ? q % L::kChunksPerRow : q / BM;
-            *reinterpret_cast<u32x4*>(tile + L::offset(row, c)) = regs[i];
+            *reinterpret_cast<u32x4*>(tile + L::offset(row, c)) = inside[i] ? regs[i] : u32x4{0u, 0u, 0u, 0u};
         }
     }
 
@@ -631,18 +677,31 @@ struct Staged {
     {
         const int tid = wave * 64 + lane;
         const int wave_m = wave >> 1, wave_n = wave & 1;
+        // Whole K steps of "regular" operands take the cheap fetch; the last, partial step and
+        // operands with other strides or alignments take the general one.
+        auto is_regular = [](int64_t s_row, int64_t s_k, bool vec) {
+            const int64_t reach = (BM - 1) * (s_row < 0 ? -s_row : s_row) + (BK - 1) * (s_k < 0 ? -s_k : s_k);
+            return (s_k == 1 ? vec : s_row == 1) && s_row >= 0 && s_k >= 0 && reach * ES < (int64_t{1} << 31);
+        };
+        const bool all_regular = is_regular(a_sm, a_sk, a_vec) && is_regular(b_sn, b_sk, b_vec);
+        const Regular pa = regular(a_sm, a_sk, a_rows, tid), pb = regular(b_sn, b_sk, b_rows, tid);
         u32x4 ra[CHUNKS], rb[CHUNKS];
-        gather(ra, a_tile, a_sm, a_sk, a_rows, k_begin, k_end, a_vec, tid);
-        gather(rb, b_tile, b_sn, b_sk, b_rows, k_begin, k_end, b_vec, tid);
+        auto fetch = [&](int k0) {
+            if (all_regular && k0 + BK <= k_end) {
+                gather_regular(ra, a_tile + ES * k0 * a_sk, a_sk, pa);
+                gather_regular(rb, b_tile + ES * k0 * b_sk, b_sk, pb);
+            } else {
+                gather(ra, a_tile, a_sm, a_sk, a_rows, k0, k_end, a_vec, tid);
+                gather(rb, b_tile, b_sn, b_sk, b_rows, k0, k_end, b_vec, tid);
+            }
+        };
+        fetch(k_begin);
         for (int k0 = k_begin; k0 < k_end; k0 += BK) {
             __syncthreads();  // the previous step's fragment reads are finished
-            commit(ra, lds, a_sk == 1, tid);
-            commit(rb, lds + A_BYTES, b_sk == 1, tid);
+            commit(ra, pa.inside, lds, a_sk == 1, tid);
+            commit(rb, pb.inside, lds + A_BYTES, b_sk == 1, tid);
             __syncthreads();
-            if (k0 + BK < k_end) {  // next step's operands travel while this one computes
-                gather(ra, a_tile, a_sm, a_sk, a_rows, k0 + BK, k_end, a_vec, tid);
-                gather(rb, b_tile, b_sn, b_sk, b_rows, k0 + BK, k_end, b_vec, tid);
-            }
+            if (k0 + BK < k_end) fetch(k0 + BK);  // next step's operands travel while this one computes
 #pragma unroll
             for (int ks = 0; ks < KSUB; ++ks) {
                 frag_t fa[MT], fb[NT];
