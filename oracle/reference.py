@@ -17,6 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_oracle.c")
+_SCAN_SRC = os.path.join(_HERE, "scan_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_oracle.so")
 _lib = None
 
@@ -26,11 +27,11 @@ _DTYPE_CODE = {"bf16": 0, "f16": 1}
 def build_oracle(force: bool = False) -> str:
     """Compile the C oracle with gcc (OpenMP over output entries)."""
     stale = (not os.path.exists(_LIB)
-             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SCAN_SRC)))
     if force or stale:
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
-             "-fno-fast-math", "-ffp-contract=off", _SRC, "-o", _LIB, "-lm"])
+             "-fno-fast-math", "-ffp-contract=off", _SRC, _SCAN_SRC, "-o", _LIB, "-lm"])
     return _LIB
 
 
@@ -52,6 +53,8 @@ def _load():
         lib.prism_oracle_decode_f16.argtypes = [ctypes.c_uint16]
         lib.prism_oracle_decode_f16.restype = dbl
         lib.prism_oracle_threads.restype = ctypes.c_int
+        lib.prism_oracle_inclusive_scan_u32.argtypes = [vp, vp, i64]
+        lib.prism_oracle_inclusive_scan_u32.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -130,3 +133,14 @@ def gemm_ref_workload(w, inputs: dict, *, batch_index: int = 0,
                     layout_a=w.layout_a, layout_b=w.layout_b,
                     alpha=w.alpha, beta=w.beta, bias=inputs.get("bias"), rows=rows,
                     c_in=None if w.beta == 0.0 else inputs["C_in"][batch_index].astype(np.float64))
+
+
+def inclusive_scan_u32_ref(x: np.ndarray) -> np.ndarray:
+    """Inclusive prefix sum modulo 2^32 of a uint32 array (the C oracle's running sum)."""
+    x = np.ascontiguousarray(x)
+    assert x.dtype == np.uint32 and x.ndim == 1
+    out = np.empty_like(x)
+    rc = _load().prism_oracle_inclusive_scan_u32(_ptr(x), _ptr(out), x.size)
+    if rc != 0:
+        raise ValueError("the oracle rejected its arguments")
+    return out

@@ -88,3 +88,11 @@ def encode(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "f32":
         return np.asarray(x, dtype=np.float32)
     raise ValueError(dtype)
+
+
+def scan_input_u32(seed: int, n: int) -> np.ndarray:
+    """n uint32 values covering the full 32-bit range (prefix sums wrap often)."""
+    out = np.empty(n, dtype=np.uint32)
+    for s, c in _slabs(n):
+        out[s:s + c] = (_hash(seed, 5, s, c, 0) >> _U64(32)).astype(np.uint32)
+    return out
