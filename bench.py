@@ -65,6 +65,66 @@ def calibrate_copy(n_bytes: int, reps: int) -> int:
     return 0
 
 
+def bench_scan(args) -> int:
+    """The prefix-scan workload: n uint32 values far beyond the caches, out of place."""
+    import numpy as np
+    import torch
+    import paper_2511_11939_amd as P
+    from workloads import scan_input_u32
+
+    n = 1 << 28
+    torch.cuda.set_device(0)
+    x = scan_input_u32(0x5EED0007, n)
+    d_in = torch.from_numpy(x.view(np.int32)).cuda()
+    d_out = torch.empty_like(d_in)
+    s, ws_bytes = P.prism_scan_workspace_size(n)
+    assert s == 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        P.scan_u32(d_in, d_out, n, ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert P.prism_scan_check(ws, stream.cuda_stream) == 0
+    launch_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+    nbytes = 8.0 * n                                  # every element read once and written once
+    gbs = nbytes / (ms_per_step * 1e-3) / 1e9
+    achieved = nbytes / (launch_ms * 1e-3) / 1e9
+    out = {
+        "metric": "uint32 inclusive prefix scan GB/s (8 bytes per element) and % of MI355X HBM peak (1 GPU)",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "scan_u32_2p28", "n": n, "tile": 4096, "workgroups": (n + 4095) // 4096},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None, "kernel": "scan_lookback",
+                     "launch_us": round(launch_ms * 1e3, 2)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import inclusive_scan_u32_ref
+        t0 = time.perf_counter()
+        ref = inclusive_scan_u32_ref(x)
+        cpu_s = time.perf_counter() - t0
+        got = d_out.cpu().numpy().view(np.uint32)
+        out["cpu_baseline"] = {"value": round(nbytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"all {n} elements, {cpu_s:.2f} s wall"}
+        out["parity_on_sample"] = {"ok": bool((got == ref).all()), "mismatches": int((got != ref).sum())}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +142,8 @@ def main() -> int:
         print("bench.py: this library runs on one GPU; --gpus must be 1 "
               "(there is no multi-GPU path to measure)", file=sys.stderr)
         return 2
+    if args.workload == "scan_u32_2p28":
+        return bench_scan(args)
 
     import numpy as np
     import torch

@@ -1,0 +1,67 @@
+/*
+ * prism_scan.h -- C ABI of the single-pass prefix scan on one MI355X (gfx950).
+ *
+ * The paper's second benchmark (section 6.1): the inclusive prefix sum of an
+ * array of 32-bit unsigned integers,
+ *
+ *     out[i] = (in[0] + in[1] + ... + in[i]) mod 2^32,
+ *
+ * computed in ONE pass over the data with the decoupled look-back scheme the
+ * paper implements (every tile publishes its aggregate, then looks back over
+ * the tiles before it until it meets one whose full prefix is known).  The
+ * data is read once and written once: 8 bytes of HBM traffic per element.
+ *
+ * Ownership, streams and errors as in prism_gemm.h: device pointers belong to
+ * the caller, the library allocates nothing, calls enqueue work on the given
+ * HIP stream and return without synchronising, argument errors are found on
+ * the host before anything is launched.
+ */
+#ifndef PRISM_SCAN_H
+#define PRISM_SCAN_H
+
+#include "prism_gemm.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Bytes of device workspace a scan of n elements needs (tile counter, error
+ * word and one 8-byte status word per tile of 4096 elements).  n < 0 is
+ * PRISM_ERR_INVALID_ARG.  Host arithmetic only.
+ */
+PRISM_API prism_status_t prism_scan_workspace_size(int64_t n, size_t* bytes_out);
+
+/*
+ * Inclusive prefix sum of n uint32 values.
+ *
+ * in, out      device, 4-byte aligned; out may be the same pointer as in (the
+ *              scan then works in place, as the paper's kernel does); any other
+ *              overlap is PRISM_ERR_INVALID_ARG.  16-byte aligned pointers take
+ *              the vector path, others a slower element-wise one.
+ * n            number of elements, 0 <= n < 2^43; n == 0 launches nothing.
+ * workspace    device, 8-byte aligned, at least prism_scan_workspace_size(n)
+ *              bytes (else PRISM_ERR_WORKSPACE); it is initialised by the call
+ *              itself and may be reused by the next call on the same stream.
+ *              Calls that overlap in time need separate workspaces.
+ * hip_stream   a hipStream_t passed as void*; NULL is the default stream.
+ *
+ * A tile waits for the tiles before it with a bounded number of polls; if the
+ * bound is ever hit (it is not in a working system: tiles take their numbers
+ * from an atomic counter, so every tile waited for is already running) the
+ * kernel still terminates, the result is wrong, and prism_scan_check reports it.
+ */
+PRISM_API prism_status_t prism_scan_u32(const uint32_t* in, uint32_t* out, int64_t n,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Synchronises the stream and reads the workspace's error word back:
+ * PRISM_OK, or PRISM_ERR_LAUNCH when a look-back of the last scan that used
+ * this workspace gave up waiting.
+ */
+PRISM_API prism_status_t prism_scan_check(const void* workspace, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRISM_SCAN_H */

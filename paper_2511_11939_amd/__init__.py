@@ -1,4 +1,5 @@
-"""MI355X (gfx950) dense GEMM library: Python binding of the C ABI in include/prism_gemm.h.
+"""MI355X (gfx950) dense GEMM and prefix-scan library: Python binding of the C ABI in
+include/prism_gemm.h and include/prism_scan.h.
 
 Everything numeric runs in the HIP kernels of libprism_gemm.so; this package
 only marshals arguments.  There is no CPU fallback: without the built library
@@ -10,4 +11,5 @@ from .binding import (  # noqa: F401
     prism_gemm, prism_gemm_batched, prism_gemm_workspace_size, prism_gemm_plan,
     prism_sched_map, prism_status_string, prism_version,
     gemm, make_desc,
+    prism_scan_workspace_size, prism_scan_u32, prism_scan_check, scan_u32,
 )

@@ -97,6 +97,12 @@ def load_library():
     lib.prism_status_string.argtypes = [ctypes.c_int]
     lib.prism_status_string.restype = ctypes.c_char_p
     lib.prism_version.restype = ctypes.c_int
+    lib.prism_scan_workspace_size.argtypes = [i64, ctypes.POINTER(sz)]
+    lib.prism_scan_workspace_size.restype = ctypes.c_int
+    lib.prism_scan_u32.argtypes = [vp, vp, i64, vp, sz, vp]
+    lib.prism_scan_u32.restype = ctypes.c_int
+    lib.prism_scan_check.argtypes = [vp, vp]
+    lib.prism_scan_check.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -205,3 +211,34 @@ def gemm(A, B, C, *, M, N, K, desc: GemmDesc, lda=None, ldb=None, ldc=None, batc
                                C, max(ldc, 1), strideC, batch, stream)
     if s != Status.OK:
         raise PrismError(s, "prism_gemm")
+
+
+# ---- prefix scan (include/prism_scan.h) ------------------------------------------------------
+
+def prism_scan_workspace_size(n):
+    out = ctypes.c_size_t(0)
+    s = load_library().prism_scan_workspace_size(n, ctypes.byref(out))
+    return s, out.value
+
+
+def prism_scan_u32(inp, out, n, workspace, workspace_bytes, hip_stream=None) -> int:
+    return load_library().prism_scan_u32(_p(inp), _p(out), n, _p(workspace), workspace_bytes, _p(hip_stream))
+
+
+def prism_scan_check(workspace, hip_stream=None) -> int:
+    return load_library().prism_scan_check(_p(workspace), _p(hip_stream))
+
+
+def scan_u32(inp, out, n, workspace, *, stream=None):
+    """Enqueue the inclusive uint32 prefix sum of `inp` into `out` (may be the same tensor) on
+    `stream` (torch stream, raw hipStream_t or None for torch's current stream).  `workspace`:
+    a device tensor of at least prism_scan_workspace_size(n) bytes.  Raises on a bad status."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    s = prism_scan_u32(inp, out, n, workspace, nbytes, stream)
+    if s != Status.OK:
+        raise PrismError(s, "prism_scan_u32")

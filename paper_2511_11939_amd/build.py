@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libprism_gemm.so")
-_UNITS = ["kernels.hip", "host_api.hip"]
+_UNITS = ["kernels.hip", "host_api.hip", "scan.hip"]
 _FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     # keep the compiler from forming packed fp32 vector ops out of scalar float code
@@ -18,8 +18,9 @@ _FLAGS = [
 
 
 def _sources():
-    out = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))]
+    out = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if not f.endswith(".o")]
     out.append(os.path.join(os.path.dirname(_HERE), "include", "prism_gemm.h"))
+    out.append(os.path.join(os.path.dirname(_HERE), "include", "prism_scan.h"))
     return out
 
 

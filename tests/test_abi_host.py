@@ -14,14 +14,15 @@ S = P.Status
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "prism_gemm.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("prism_gemm.h", "prism_scan.h"))
     return sorted(set(re.findall(r"PRISM_API[^;(]*?\b(prism_\w+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"prism_gemm", "prism_gemm_batched", "prism_gemm_workspace_size", "prism_gemm_plan",
-            "prism_sched_map", "prism_status_string", "prism_version"} <= set(names)
+            "prism_sched_map", "prism_status_string", "prism_version",
+            "prism_scan_workspace_size", "prism_scan_u32", "prism_scan_check"} <= set(names)
     lib = ctypes.CDLL(P.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -195,3 +196,25 @@ def test_fp32_operands_need_an_fp32_result():
     assert P.prism_gemm(d, 64, 64, 64, FAKE_A, 64, FAKE_B, 64, FAKE_A + 64 * 64 * 4 - 4, 64, None) == S.INVALID_ARG
     s, _ = P.prism_gemm_plan(d, 64, 64, 64, FAKE_A, 64, 0, FAKE_B, 64, 0, FAKE_A + 64 * 64 * 4, 64, 0, 1)
     assert s == S.OK
+
+
+def test_scan_host_validation():
+    s, b = P.prism_scan_workspace_size(0)
+    assert (s, b) == (S.OK, 0)
+    s, b = P.prism_scan_workspace_size(1)
+    assert (s, b) == (S.OK, 64 + 8)
+    s, b = P.prism_scan_workspace_size(4096 * 10 + 1)
+    assert (s, b) == (S.OK, 64 + 8 * 11)
+    assert P.prism_scan_workspace_size(-1)[0] == S.INVALID_ARG
+    assert P.prism_scan_workspace_size(1 << 43)[0] == S.INVALID_ARG
+    IN, OUT, WS = FAKE, FAKE + (1 << 32), FAKE + (2 << 32)
+    assert P.prism_scan_u32(None, None, 0, None, 0, None) == S.OK              # nothing to do
+    assert P.prism_scan_u32(None, OUT, 100, WS, 1 << 20, None) == S.INVALID_ARG
+    assert P.prism_scan_u32(IN, OUT, -5, WS, 1 << 20, None) == S.INVALID_ARG
+    assert P.prism_scan_u32(IN + 2, OUT, 100, WS, 1 << 20, None) == S.INVALID_ARG     # not 4-byte aligned
+    assert P.prism_scan_u32(IN, IN + 40, 100, WS, 1 << 20, None) == S.INVALID_ARG     # partial overlap
+    assert P.prism_scan_u32(IN, OUT, 100, None, 0, None) == S.WORKSPACE
+    assert P.prism_scan_u32(IN, OUT, 100, WS, 71, None) == S.WORKSPACE
+    assert P.prism_scan_u32(IN, OUT, 100, WS + 4, 1 << 20, None) == S.INVALID_ARG     # workspace alignment
+    assert P.prism_scan_u32(IN, OUT, 100, IN + 64, 1 << 20, None) == S.INVALID_ARG    # workspace inside the data
+    assert P.prism_scan_check(None, None) == S.INVALID_ARG
