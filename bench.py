@@ -107,7 +107,7 @@ def bench_scan(args) -> int:
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "scan_u32_2p28", "n": n, "tile": 4096, "workgroups": (n + 4095) // 4096},
+        "config": {"workload": "scan_u32_2p28", "n": n, "tile": 16384, "workgroups": (n + 16383) // 16384},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None, "kernel": "scan_lookback",
                      "launch_us": round(launch_ms * 1e3, 2)},

@@ -27,7 +27,7 @@ extern "C" {
 
 /*
  * Bytes of device workspace a scan of n elements needs (tile counter, error
- * word and one 8-byte status word per tile of 4096 elements).  n < 0 is
+ * word and one 8-byte status word per tile of 16384 elements).  n < 0 is
  * PRISM_ERR_INVALID_ARG.  Host arithmetic only.
  */
 PRISM_API prism_status_t prism_scan_workspace_size(int64_t n, size_t* bytes_out);

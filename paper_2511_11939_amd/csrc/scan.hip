@@ -5,9 +5,10 @@
 // grid-level chain of per-tile status words.
 //
 // What differs from the paper's kernel, written for 32-wide warps and 16 warps per block:
-// tiles of 4096 elements handled by four 64-wide waves, every lane owning four 16-byte
-// vectors (loads and stores are whole cache lines per wave); the four per-lane partial sums
-// are scanned together, so a tile needs one barrier for the combine and one for the prefix;
+// its tile of 16384 elements is handled by four 64-wide waves, every lane owning sixteen
+// 16-byte vectors held in registers (loads and stores are whole cache lines per wave, and
+// the data never passes through LDS); the sixteen per-lane partial sums are scanned
+// together, so a tile needs one barrier for the combine and one for the prefix;
 // the look-back is done by a whole wave, 64 predecessors per poll; a status word carries
 // flag and value in one 64-bit store, so no fence separates them.
 #include <hip/hip_runtime.h>
@@ -19,8 +20,8 @@
 namespace prism {
 namespace scan {
 
-constexpr int kThreads = 256, kWaves = 4, kVec = 4, kChunks = 4;
-constexpr int kTile = kThreads * kVec * kChunks;  // 4096 elements per workgroup
+constexpr int kThreads = 256, kWaves = 4, kVec = 4, kChunks = 16;
+constexpr int kTile = kThreads * kVec * kChunks;  // 16384 elements per workgroup, the tile of the paper's kernel
 constexpr int64_t kMaxN = int64_t{1} << 43;
 constexpr size_t kHeaderBytes = 64;               // [0] tile counter, [1] error word
 constexpr uint32_t kDefaultSpinLimit = 1u << 20;  // polls of one status word; a real wait is a few dozen
@@ -35,14 +36,25 @@ __device__ __forceinline__ uint64_t pack(uint32_t flag, uint32_t value)
 }
 
 // ---- wave level: all 64 lanes converged -------------------------------------------------
-// Inclusive sum over the lanes of a wave (lane l receives the sum of lanes 0..l).
-__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int lane)
+// Inclusive sum over the lanes of a wave (lane l receives the sum of lanes 0..l), with the
+// data-parallel-primitive lane moves of the vector ALU instead of LDS permutes: four shifts
+// inside each row of 16 lanes (lanes without a source add zero), then the last lane of a row
+// is broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.  This is
+// the gfx950 counterpart of the shuffle-up loop of the paper's `scan_warps`.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t lanes_moved(uint32_t v)
 {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t up = __shfl_up(v, d, 64);
-        if (lane >= d) v += up;
-    }
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF));
+}
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int)
+{
+    constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+    v += lanes_moved<kRowShr + 1, 0xF>(v);
+    v += lanes_moved<kRowShr + 2, 0xF>(v);
+    v += lanes_moved<kRowShr + 4, 0xF>(v);
+    v += lanes_moved<kRowShr + 8, 0xF>(v);
+    v += lanes_moved<kRowBcast15, 0xA>(v);
+    v += lanes_moved<kRowBcast31, 0xC>(v);
     return v;
 }
 
@@ -109,7 +121,7 @@ __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_
     const int64_t base = static_cast<int64_t>(tile) * kTile;
     const bool whole = base + kTile <= n;
 
-    // ---- lane level: chunk j of the tile is 1024 consecutive elements, 4 per lane
+    // ---- lane level: chunk j of the tile is 1024 consecutive elements, 4 per lane (one vector)
     uint32_t x[kChunks][kVec];
 #pragma unroll
     for (int j = 0; j < kChunks; ++j) {

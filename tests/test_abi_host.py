@@ -203,7 +203,7 @@ def test_scan_host_validation():
     assert (s, b) == (S.OK, 0)
     s, b = P.prism_scan_workspace_size(1)
     assert (s, b) == (S.OK, 64 + 8)
-    s, b = P.prism_scan_workspace_size(4096 * 10 + 1)
+    s, b = P.prism_scan_workspace_size(16384 * 10 + 1)
     assert (s, b) == (S.OK, 64 + 8 * 11)
     assert P.prism_scan_workspace_size(-1)[0] == S.INVALID_ARG
     assert P.prism_scan_workspace_size(1 << 43)[0] == S.INVALID_ARG

@@ -9,7 +9,7 @@ from oracle import inclusive_scan_u32_ref
 from workloads import scan_input_u32
 
 pytestmark = pytest.mark.gpu
-TILE = 4096
+TILE = 16384
 
 
 def _ws(n):
@@ -56,7 +56,7 @@ def test_closed_forms_and_wraparound():
 
 
 def test_many_tiles_long_look_back_chain_and_workspace_reuse():
-    """2^24 elements = 4096 tiles (windows of 64 predecessors are walked many times); the same
+    """2^24 elements = 1024 tiles (windows of 64 predecessors are walked many times); the same
     workspace serves three calls in a row, with a shorter problem in between."""
     n = 1 << 24
     ws = _ws(n)
@@ -92,7 +92,7 @@ def test_bounded_wait_gives_up_cleanly(monkeypatch):
     kernel still terminates, and either the result is right (nobody had to wait) or the
     error word says so."""
     monkeypatch.setenv("PRISM_SCAN_SPIN_LIMIT", "0")
-    n = 2000 * TILE
+    n = 1500 * TILE
     x = scan_input_u32(11, n)
     d = torch.from_numpy(x.view(np.int32)).cuda()
     out = torch.empty_like(d)
