@@ -45,9 +45,10 @@ def source_digest() -> str:
 # (two runs), each divided by the factor the same counter shows on a copy of known size
 # (--calibrate-copy).  Summaries under profiles/.  workload -> (bytes, digest of the sources).
 MEASURED_TRAFFIC: dict = {
-    "cfg2_4096_bf16": (235237885, "97a5f149f3f255e8"),
-    "cfg3_proj_bias": (941252150, "97a5f149f3f255e8"),
-    "cfg5_batched_512": (417631814, "97a5f149f3f255e8"),
+    "cfg2_4096_bf16": (235258222, "5c883ce54df8ed96"),
+    "cfg3_proj_bias": (941200217, "5c883ce54df8ed96"),
+    "cfg5_batched_512": (417644748, "5c883ce54df8ed96"),
+    "scan_u32_2p28": (2157018902, "5c883ce54df8ed96"),
 }
 
 
@@ -112,6 +113,9 @@ def bench_scan(args) -> int:
                      "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None, "kernel": "scan_lookback",
                      "launch_us": round(launch_ms * 1e3, 2)},
     }
+    measured = MEASURED_TRAFFIC.get("scan_u32_2p28")
+    if measured and measured[1] == source_digest():
+        out["roofline"]["traffic"] = measured[0]
     if not args.no_cpu_baseline:
         from oracle import inclusive_scan_u32_ref
         t0 = time.perf_counter()
