@@ -43,17 +43,18 @@ __device__ __forceinline__ Placement place(const GemmParams& p, int wg)
 // must call it (it starts with a barrier that retires the slots).  OWN_PATCH true: `patch`
 // is this wave's private 16-row patch outside the slots; no barrier, 16 rows per pass.
 template <typename TileT, int MT, int NT, bool OWN_PATCH = false>
-__device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q, const TileT& acc,
+__device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams& p, const Placement& q, const TileT& acc,
                                          int m_wave, int n_wave, char* lds, int wave, int lane)
 {
+    const persp::Wave wv = wgp.wave();
     char* patch = lds;
     if constexpr (!OWN_PATCH) {
-        __syncthreads();
+        wg::sync(wgp);
         patch = lds + wave * wg::drain_patch_bytes(NT);
     }
     auto drain_any = [&](auto&& sink) {
-        if constexpr (OWN_PATCH) wg::drain<MT, NT, 16, 0>(acc, patch, lane, sink);
-        else wg::drain<MT, NT>(acc, patch, lane, sink);
+        if constexpr (OWN_PATCH) wg::drain<MT, NT, 16, 0>(wv, acc, patch, lane, sink);
+        else wg::drain<MT, NT>(wv, acc, patch, lane, sink);
     };
     if (p.split_k > 1) {
         float* slab = p.partial + (static_cast<int64_t>(q.batch) * p.split_k + q.slice) * p.M * p.N;
@@ -86,8 +87,8 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
                 grid::finish_run<OUT>(row + (lane_off + static_cast<uint32_t>(r_lane) * static_cast<uint32_t>(row_bytes)),
                                       p.alpha, bias, lo, hi);
             };
-            if constexpr (OWN_PATCH) wg::drain_runs16<MT, NT>(acc, patch, lane, sink);
-            else wg::drain_runs<MT, NT>(acc, patch, lane, sink);
+            if constexpr (OWN_PATCH) wg::drain_runs16<MT, NT>(wv, acc, patch, lane, sink);
+            else wg::drain_runs<MT, NT>(wv, acc, patch, lane, sink);
         };
         if (p.c_dtype == DT_BF16) run(std::integral_constant<int, DT_BF16>{});
         else if (p.c_dtype == DT_F16) run(std::integral_constant<int, DT_F16>{});
@@ -100,6 +101,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const Placement& q
 template <typename P, int BM, int BN, int BK, int WAVES_N>
 __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
 {
+    const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
     __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -112,10 +114,10 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
 
     typename P::tile_t acc;
     acc.clear();
-    P::run(acc, a_tile, static_cast<uint32_t>(2 * p.a_sm), a_rows, b_tile, static_cast<uint32_t>(2 * p.b_sn),
+    P::run(wgp, acc, a_tile, static_cast<uint32_t>(2 * p.a_sm), a_rows, b_tile, static_cast<uint32_t>(2 * p.b_sn),
            b_rows, (q.k_end - q.k_begin) / BK, lds, wave, lane);
 
-    epilogue<typename P::tile_t, P::MT, P::NT>(p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
+    epilogue<typename P::tile_t, P::MT, P::NT>(wgp, p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
                                                q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane);
 }
 
@@ -125,6 +127,7 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
 template <typename T>
 __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const int total)
 {
+    const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
     using P = wg::PersistentPipe<T>;
     __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
     const int lane = threadIdx.x & 63;
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const
     int tile = blockIdx.x;
     Placement cur = place<P::BM, P::BN>(p, tile), nxt = cur;
     P::run(
-        lds, wave, lane, source(cur), (cur.k_end - cur.k_begin) / P::BK,
+        wgp, lds, wave, lane, source(cur), (cur.k_end - cur.k_begin) / P::BK,
         [&](typename P::Source& s, int& ksteps) {
             if (tile + static_cast<int>(gridDim.x) >= total) return false;
             nxt = place<P::BM, P::BN>(p, tile + gridDim.x);
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const
             // the K loop it would not fit in registers beside the accumulators and fragments.
             int lane_now = lane;
             asm volatile("" : "+v"(lane_now));
-            epilogue<typename P::tile_t, P::MT, P::NT, true>(p, cur, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
+            epilogue<typename P::tile_t, P::MT, P::NT, true>(wgp, p, cur, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
                                                              cur.n0 + (wave % P::WAVES_N) * P::WTN,
                                                              lds + P::PATCH_BASE + wave * P::PATCH_BYTES, wave, lane_now);
         },
@@ -169,6 +172,7 @@ __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const
 template <typename T>
 __global__ __launch_bounds__(256) void gemm_staged(const GemmParams p)
 {
+    const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
     using S = wg::Staged<T>;
     __shared__ __attribute__((aligned(1024))) char lds[S::LDS_BYTES];
     const int lane = threadIdx.x & 63;
@@ -182,10 +186,10 @@ __global__ __launch_bounds__(256) void gemm_staged(const GemmParams p)
 
     typename S::tile_t acc;
     acc.clear();
-    S::run(acc, a_tile, p.a_sm, p.a_sk, a_rows, p.a_vec != 0, b_tile, p.b_sn, p.b_sk, b_rows, p.b_vec != 0,
+    S::run(wgp, acc, a_tile, p.a_sm, p.a_sk, a_rows, p.a_vec != 0, b_tile, p.b_sn, p.b_sk, b_rows, p.b_vec != 0,
            q.k_begin, q.k_end, lds, wave, lane);
 
-    epilogue<typename S::tile_t, S::MT, S::NT>(p, q, acc, q.m0 + (wave >> 1) * S::WTM,
+    epilogue<typename S::tile_t, S::MT, S::NT>(wgp, p, q, acc, q.m0 + (wave >> 1) * S::WTM,
                                                q.n0 + (wave & 1) * S::WTN, lds, wave, lane);
 }
 

@@ -11,6 +11,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "persp.hpp"
+
 namespace prism {
 
 using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
@@ -67,7 +69,7 @@ constexpr int kBlockK = 32;
 // instruction needs for the k sum to pair the right elements.
 template <typename T, int BK>
 __device__ __forceinline__ typename Frag<T>::type
-load_fragment(const char* tile, int row0, int ksub, int lane)
+load_fragment(persp::Lane, const char* tile, int row0, int ksub, int lane)
 {
     const int row = row0 + (lane & 15);
     const int chunk = 4 * ksub + (lane >> 4);

@@ -16,6 +16,7 @@
 #include <cstdlib>
 
 #include "../../include/prism_scan.h"
+#include "persp.hpp"
 
 namespace prism {
 namespace scan {
@@ -35,6 +36,9 @@ __device__ __forceinline__ uint64_t pack(uint32_t flag, uint32_t value)
     return (static_cast<uint64_t>(flag) << 32) | value;
 }
 
+// ---- workgroup level
+__device__ __forceinline__ void sync(persp::Workgroup) { __syncthreads(); }
+
 // ---- wave level: all 64 lanes converged -------------------------------------------------
 // Inclusive sum over the lanes of a wave (lane l receives the sum of lanes 0..l), with the
 // data-parallel-primitive lane moves of the vector ALU instead of LDS permutes: four shifts
@@ -46,7 +50,7 @@ __device__ __forceinline__ uint32_t lanes_moved(uint32_t v)
 {
     return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF));
 }
-__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int)
+__device__ __forceinline__ uint32_t wave_inclusive_sum(persp::Wave, uint32_t v)
 {
     constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
     v += lanes_moved<kRowShr + 1, 0xF>(v);
@@ -62,7 +66,7 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int)
 // Called by one whole wave of tile `tile` (> 0) after its aggregate is published.  Returns,
 // in every lane, the sum of all elements before the tile.  Lane l looks at tile
 // (window_end - l); the nearest predecessor whose full prefix is known ends the walk.
-__device__ __forceinline__ uint32_t look_back(const uint64_t* status, uint32_t tile, int lane, uint32_t spin_limit,
+__device__ __forceinline__ uint32_t look_back(persp::Wave, const uint64_t* status, uint32_t tile, int lane, uint32_t spin_limit,
                                               uint32_t* error_word)
 {
     uint32_t exclusive = 0;
@@ -109,6 +113,8 @@ template <bool VEC_IN, bool VEC_OUT>
 __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_t* out, int64_t n, uint32_t* header,
                                                      uint64_t* status, uint32_t spin_limit)
 {
+    const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
+    const persp::Wave wv = wgp.wave();
     __shared__ uint32_t s_tile, s_exclusive;
     __shared__ uint32_t s_wave_total[kChunks][kWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_
     // Tiles are numbered in the order workgroups start, so every tile this one will wait
     // for has been taken by a workgroup that is already running.
     if (tid == 0) s_tile = __hip_atomic_fetch_add(header, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
+    sync(wgp);
     const uint32_t tile = s_tile;
     const int64_t base = static_cast<int64_t>(tile) * kTile;
     const bool whole = base + kTile <= n;
@@ -142,11 +148,11 @@ __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_
     uint32_t before[kChunks];  // sum of the chunk's elements in lower lanes of this wave
 #pragma unroll
     for (int j = 0; j < kChunks; ++j) {
-        const uint32_t incl = wave_inclusive_sum(x[j][kVec - 1], lane);
+        const uint32_t incl = wave_inclusive_sum(wv, x[j][kVec - 1]);
         before[j] = incl - x[j][kVec - 1];
         if (lane == 63) s_wave_total[j][wave] = incl;
     }
-    __syncthreads();
+    sync(wgp);
 
     // ---- workgroup level: chunks in order, waves in order inside a chunk
     uint32_t running = 0;
@@ -170,14 +176,14 @@ __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_
         } else {
             if (lane == 0)
                 __hip_atomic_store(status + tile, pack(kAggregate, aggregate), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            exclusive = look_back(status, tile, lane, spin_limit, header + 1);
+            exclusive = look_back(wv, status, tile, lane, spin_limit, header + 1);
             if (lane == 0)
                 __hip_atomic_store(status + tile, pack(kPrefix, exclusive + aggregate), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
         if (lane == 0) s_exclusive = exclusive;
     }
-    __syncthreads();
+    sync(wgp);
     const uint32_t exclusive = s_exclusive;
 
 #pragma unroll

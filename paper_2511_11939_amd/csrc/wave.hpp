@@ -4,7 +4,7 @@
 // `mma.sync` / warpgroup-collective `wgmma` the paper builds its kernels on
 // (sections 2.3 and 6.2): it only means something when a whole, aligned group
 // of lanes executes it, so these functions must be called with the complete
-// wavefront converged.
+// wavefront converged: each takes a persp::Wave token, which per-lane code cannot obtain.
 #pragma once
 
 #include "lane.hpp"
@@ -19,18 +19,18 @@ namespace wave {
 // gfx950 this one needs less energy per multiply-add (a quarter of the
 // accumulator registers are read and written per instruction), and on this
 // power-limited part that shows directly as a higher sustained clock.
-__device__ __forceinline__ f32x4 mfma_block(bf16x8 r, bf16x8 c, f32x4 acc)
+__device__ __forceinline__ f32x4 mfma_block(persp::Wave, bf16x8 r, bf16x8 c, f32x4 acc)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(r, c, acc, 0, 0, 0);
 }
-__device__ __forceinline__ f32x4 mfma_block(f16x8 r, f16x8 c, f32x4 acc)
+__device__ __forceinline__ f32x4 mfma_block(persp::Wave, f16x8 r, f16x8 c, f32x4 acc)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(r, c, acc, 0, 0, 0);
 }
 
 // fp32 operands: a fragment holds 4 consecutive k per lane; MFMA e of the four takes element
 // e of both fragments, so lane group g (lane/16) contributes k = 4g + e to it.
-__device__ __forceinline__ f32x4 mfma_block(f32x4 r, f32x4 c, f32x4 acc)
+__device__ __forceinline__ f32x4 mfma_block(persp::Wave, f32x4 r, f32x4 c, f32x4 acc)
 {
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(r[e], c[e], acc, 0, 0, 0);
@@ -54,23 +54,23 @@ struct Tile {
     }
 
     // one 32-wide k sub-step over the whole wave tile
-    __device__ __forceinline__ void mma(const frag_t (&a)[MT], const frag_t (&b)[NT])
+    __device__ __forceinline__ void mma(persp::Wave w, const frag_t (&a)[MT], const frag_t (&b)[NT])
     {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < NT; ++j) acc[i][j] = mfma_block(b[j], a[i], acc[i][j]);
+            for (int j = 0; j < NT; ++j) acc[i][j] = mfma_block(w, b[j], a[i], acc[i][j]);
     }
 };
 
 // Fragments of one k sub-step for a wave tile whose first row in the LDS tile
 // is row0: MT (or NT) blocks of 16 rows.
 template <typename T, int BK, int NBLK>
-__device__ __forceinline__ void load_fragments(typename Frag<T>::type (&f)[NBLK], const char* tile,
+__device__ __forceinline__ void load_fragments(persp::Wave w, typename Frag<T>::type (&f)[NBLK], const char* tile,
                                                int row0, int ksub, int lane)
 {
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) f[i] = lane::load_fragment<T, BK>(tile, row0 + lane::kBlock * i, ksub, lane);
+    for (int i = 0; i < NBLK; ++i) f[i] = lane::load_fragment<T, BK>(w.lane(), tile, row0 + lane::kBlock * i, ksub, lane);
 }
 
 }  // namespace wave

@@ -50,7 +50,15 @@ __device__ __forceinline__ const char* scalarize(const char* p)
     return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
-__device__ __forceinline__ void copy_async_16(const char* uniform_base, uint32_t lane_offset,
+// Workgroup barrier: only code that holds the workgroup token -- code every wave of the
+// workgroup executes -- can reach it (the paper's block-level synchronisation, section 3.5).
+__device__ __forceinline__ void barrier(persp::Workgroup) { __builtin_amdgcn_s_barrier(); }
+// Barrier that also waits for the caller's outstanding LDS and memory operations.
+__device__ __forceinline__ void sync(persp::Workgroup) { __syncthreads(); }
+
+// One wave-wide copy of 64 x 16 bytes from global memory straight into LDS: lane l's bytes
+// land at lds_addr + 16*l.  Wave-level: base and LDS address are per-wave values.
+__device__ __forceinline__ void copy_async_16(persp::Wave, const char* uniform_base, uint32_t lane_offset,
                                               uint32_t lds_addr)
 {
     uniform_base = scalarize(uniform_base);  // no-ops when the values already live in SGPRs
@@ -74,7 +82,7 @@ constexpr int drain_patch_bytes(int nt) { return kDrainRows * (lane::kBlock * nt
 // ROWS: rows per pass (32 = two blocks, 16 = one); PAD: floats of row padding (4 keeps the
 // accesses free of bank conflicts, 0 fits 16 rows of a 128-wide tile into 8 KiB).
 template <int MT, int NT, int ROWS = kDrainRows, int PAD = 4, typename TileT, typename Sink>
-__device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, Sink&& sink)
+__device__ __forceinline__ void drain(persp::Wave, const TileT& acc, char* patch, int lane, Sink&& sink)
 {
     static_assert(ROWS == 16 || (ROWS == 32 && MT % 2 == 0), "a pass takes one or two 16-row blocks");
     constexpr int BLOCKS = ROWS / lane::kBlock;
@@ -111,7 +119,7 @@ __device__ __forceinline__ void drain(const TileT& acc, char* patch, int lane, S
 // Inside a patch row the 16-byte units are stored evens first, odds second, so
 // that both the writes and the two reads of a run are spread over all banks.
 template <int MT, int NT, typename TileT, typename Sink>
-__device__ __forceinline__ void drain_runs(const TileT& acc, char* patch, int lane, Sink&& sink)
+__device__ __forceinline__ void drain_runs(persp::Wave, const TileT& acc, char* patch, int lane, Sink&& sink)
 {
     static_assert(MT % 2 == 0, "a pass takes two 16-row blocks");
     constexpr int WTN = lane::kBlock * NT;
@@ -186,10 +194,11 @@ struct Pipeline {
     //                           fragment reads of (t+1, 0) dealt between them.
     // Every piece is pinned with a scheduling fence so the matrix pipe always
     // has the next MFMA queued while the memory instructions issue.
-    __device__ __forceinline__ static void run(tile_t& acc, const char* a_tile, uint32_t a_ld, int a_rows,
+    __device__ __forceinline__ static void run(persp::Workgroup wgp, tile_t& acc, const char* a_tile, uint32_t a_ld, int a_rows,
                                const char* b_tile, uint32_t b_ld, int b_rows, int ksteps,
                                char* lds, int wave, int lane)
     {
+        const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
         constexpr int NM = MT * NT;   // MFMAs per sub-step
         constexpr int NR = MT + NT;   // fragment reads per sub-step
         // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave) of COPY_ROWS rows;
@@ -215,8 +224,8 @@ struct Pipeline {
         auto copy = [&](int c, int step, int stage) {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(a_tile + k_bytes, g_off[c], slot + c * NW * 1024);
-            else copy_async_16(b_tile + k_bytes, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
+            if (c < A_COPIES) copy_async_16(wv, a_tile + k_bytes, g_off[c], slot + c * NW * 1024);
+            else copy_async_16(wv, b_tile + k_bytes, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
         };
 
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
@@ -226,13 +235,13 @@ struct Pipeline {
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
         auto read = [&](int r, int buf, int stage, int ksub) {
             const char* st = lds + stage * STAGE_BYTES;
-            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(st, a_row0, ksub, lane);
-            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
-            else fa[buf][r - NT] = lane::load_fragment<T, BK>(st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
+            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
+            else fa[buf][r - NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
         };
         auto mfma = [&](int m, int buf) {
             const int i = m / NT, j = m % NT;
-            acc.acc[i][j] = wave::mfma_block(fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
 
         // -- prologue: fill the slots, wait for step 0, fetch its first fragments
@@ -244,7 +253,7 @@ struct Pipeline {
             }
         if (ksteps >= STAGES) wait_counts<(STAGES - 1) * COPIES, 0>();
         else wait_counts<0, 0>();
-        __builtin_amdgcn_s_barrier();
+        barrier(wgp);
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
@@ -292,7 +301,7 @@ struct Pipeline {
                     // Hand-over: my copies for step t+1 have landed and my reads of this
                     // slot are done; after the barrier that holds for every wave.
                     wait_counts<0, 0>();
-                    __builtin_amdgcn_s_barrier();
+                    barrier(wgp);
                     asm volatile("" ::: "memory");  // keep what follows on this side of the barrier
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -342,7 +351,7 @@ struct Pipeline {
 // position p of row r is kept at position p ^ r (positions as in drain_runs: even units
 // first), which spreads the 16 rows of a write and the 16 units of a read over the banks.
 template <int MT, int NT, typename TileT, typename Sink>
-__device__ __forceinline__ void drain_runs16(const TileT& acc, char* patch, int lane, Sink&& sink)
+__device__ __forceinline__ void drain_runs16(persp::Wave, const TileT& acc, char* patch, int lane, Sink&& sink)
 {
     constexpr int WTN = lane::kBlock * NT;
     constexpr int UNITS = WTN / 4;
@@ -420,9 +429,10 @@ struct PersistentPipe {
     //   finish(tile_t&): epilogue of the current tile (its accumulators are complete)
     //   advance(): the tile described by the last peek becomes the current one
     template <typename Peek, typename Finish, typename Advance>
-    __device__ __forceinline__ static void run(char* lds, int wave, int lane, Source first, int first_ksteps,
+    __device__ __forceinline__ static void run(persp::Workgroup wgp, char* lds, int wave, int lane, Source first, int first_ksteps,
                                                Peek&& peek, Finish&& finish, Advance&& advance)
     {
+        const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
         tile_t acc;
         frag_t fa[2][MT], fb[2][NT];
         uint32_t g_off[COPIES];
@@ -445,18 +455,18 @@ struct PersistentPipe {
         // copy number c of the K step whose operands start at a_src / b_src, into slot `stage`
         auto copy = [&](int c, const char* a_src, const char* b_src, int stage) {
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(a_src, g_off[c], slot + c * NW * 1024);
-            else copy_async_16(b_src, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
+            if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], slot + c * NW * 1024);
+            else copy_async_16(wv, b_src, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
         };
         auto read = [&](int r, int buf, int stage, int ksub) {
             const char* st = lds + stage * STAGE_BYTES;
-            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(st, a_row0, ksub, lane);
-            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
-            else fa[buf][r - NT] = lane::load_fragment<T, BK>(st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
+            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
+            else fa[buf][r - NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
         };
         auto mfma = [&](int m, int buf) {
             const int i = m / NT, j = m % NT;
-            acc.acc[i][j] = wave::mfma_block(fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
         auto read_slot = [](int r) constexpr { return 2 * r; };
         auto copy_slot = [](int c) constexpr { return 2 * c + 1; };
@@ -485,7 +495,7 @@ struct PersistentPipe {
             }
             if (switch_now) set_offsets(to);
             wait_counts<0, 0>();
-            __builtin_amdgcn_s_barrier();
+            barrier(wgp);
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -519,7 +529,7 @@ struct PersistentPipe {
 #pragma unroll
         for (int c = 0; c < TAILN; ++c) copy(c, sc.a + STEP, sc.b + STEP, 1);
         wait_counts<TAILN, 0>();
-        __builtin_amdgcn_s_barrier();
+        barrier(wgp);
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
@@ -671,10 +681,11 @@ struct Staged {
         }
     }
 
-    __device__ __forceinline__ static void run(tile_t& acc, const char* a_tile, int64_t a_sm, int64_t a_sk, int a_rows, bool a_vec,
+    __device__ __forceinline__ static void run(persp::Workgroup wgp, tile_t& acc, const char* a_tile, int64_t a_sm, int64_t a_sk, int a_rows, bool a_vec,
                                const char* b_tile, int64_t b_sn, int64_t b_sk, int b_rows, bool b_vec,
                                int k_begin, int k_end, char* lds, int wave, int lane)
     {
+        const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
         const int tid = wave * 64 + lane;
         const int wave_m = wave >> 1, wave_n = wave & 1;
         // Whole K steps of "regular" operands take the cheap fetch; the last, partial step and
@@ -697,17 +708,17 @@ struct Staged {
         };
         fetch(k_begin);
         for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-            __syncthreads();  // the previous step's fragment reads are finished
+            sync(wgp);  // the previous step's fragment reads are finished
             commit(ra, pa.inside, lds, a_sk == 1, tid);
             commit(rb, pb.inside, lds + A_BYTES, b_sk == 1, tid);
-            __syncthreads();
+            sync(wgp);
             if (k0 + BK < k_end) fetch(k0 + BK);  // next step's operands travel while this one computes
 #pragma unroll
             for (int ks = 0; ks < KSUB; ++ks) {
                 frag_t fa[MT], fb[NT];
-                wave::load_fragments<T, 64, MT>(fa, lds, wave_m * WTM, ks, lane);
-                wave::load_fragments<T, 64, NT>(fb, lds + A_BYTES, wave_n * WTN, ks, lane);
-                acc.mma(fa, fb);
+                wave::load_fragments<T, 64, MT>(wv, fa, lds, wave_m * WTM, ks, lane);
+                wave::load_fragments<T, 64, NT>(wv, fb, lds + A_BYTES, wave_n * WTN, ks, lane);
+                acc.mma(wv, fa, fb);
             }
         }
     }

@@ -1,0 +1,9 @@
+// MUST NOT COMPILE: there is no way from a lane back up to its wave.
+// EXPECT: no member named 'wave' in 'prism::persp::Lane'
+#include "workgroup.hpp"
+using namespace prism;
+__device__ void per_lane(persp::Lane l)
+{
+    persp::Wave w = l.wave();
+    (void)w;
+}
