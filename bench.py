@@ -52,6 +52,24 @@ MEASURED_TRAFFIC: dict = {
 }
 
 
+def copy_ceiling_gbs(n_bytes: int = 1 << 28, reps: int = 20) -> float:
+    """What a plain device copy reaches on this machine right now (bytes read + bytes written per
+    second): context for the HBM-bound workloads, measured with events on torch's stream."""
+    import torch
+    src = torch.ones(n_bytes // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def calibrate_copy(n_bytes: int, reps: int) -> int:
     """A plain device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -116,6 +134,7 @@ def bench_scan(args) -> int:
     measured = MEASURED_TRAFFIC.get("scan_u32_2p28")
     if measured and measured[1] == source_digest():
         out["roofline"]["traffic"] = measured[0]
+    out["roofline"]["device_copy_gbs"] = round(copy_ceiling_gbs(), 1)
     if not args.no_cpu_baseline:
         from oracle import inclusive_scan_u32_ref
         t0 = time.perf_counter()
@@ -209,7 +228,8 @@ def main() -> int:
     else:
         achieved = algorithmic_bytes(w) / (launch_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "device_copy_gbs": round(copy_ceiling_gbs(), 1)}
     roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent"}.get(plan.kernel, "none")
     roofline["launch_us"] = round(launch_ms * 1e3, 2)
     measured = MEASURED_TRAFFIC.get(w.name)
