@@ -221,7 +221,7 @@ struct Pipeline {
         const uint32_t lds0 = lds_address(lds) + wave * 1024;
 
         // copy number c (0 .. COPIES-1) of K step `step` into slot `stage`
-        auto copy = [&](int c, int step, int stage) {
+        auto copy = [&](int c, int step, int stage) __attribute__((always_inline)) {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
             if (c < A_COPIES) copy_async_16(wv, a_tile + k_bytes, g_off[c], slot + c * NW * 1024);
@@ -233,13 +233,13 @@ struct Pipeline {
         frag_t fa[2][MT], fb[2][NT];
         // read number r (0 .. NR-1) of sub-step ksub of slot `stage` into buffer `buf`;
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
-        auto read = [&](int r, int buf, int stage, int ksub) {
+        auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES;
             if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
             else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
             else fa[buf][r - NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
         };
-        auto mfma = [&](int m, int buf) {
+        auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
             const int i = m / NT, j = m % NT;
             acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
@@ -260,13 +260,15 @@ struct Pipeline {
 
         // MFMA slots of the memory instructions of a group: reads on the even slots, copies on
         // the odd ones, so no MFMA has more than one of them in its 16-cycle shadow.
-        auto read_slot = [](int r) constexpr { return 2 * r < NM ? 2 * r : r % NM; };
-        auto copy_slot = [](int c) constexpr { return 2 * c + 1 < NM ? 2 * c + 1 : c % NM; };
-        // The first TAILN copies of a step are issued right after the slot is released, one
-        // every TAIL_SPACING MFMAs; the last HEADN at the start of the following step.
+        // Read r sits on slot 2r, head copy c on slot 2c+1, tail copy c on slot
+        // TAIL_SPACING*c+1.  The first TAILN copies of a step are issued right after the slot
+        // is released, the last HEADN at the start of the following step.  (The slot of an
+        // instruction is computed from the slot index, not searched for: the loops below are
+        // unrolled in full, and their size before unrolling is limited.)
         constexpr int HEADN = COPIES / 4, TAILN = COPIES - HEADN;
-        constexpr int TAIL_SPACING = (NM - 2) / TAILN >= 4 ? 4 : ((NM - 2) / TAILN >= 2 ? 2 : 1);
-        auto tail_slot = [](int c) constexpr { return (TAIL_SPACING * c + 1) % NM; };
+        constexpr int TAIL_SPACING = 4 * (TAILN - 1) + 1 < NM ? 4 : 2;
+        static_assert(2 * NR <= NM && 2 * HEADN <= NM && TAIL_SPACING * (TAILN - 1) + 1 < NM,
+                      "every memory instruction of a group needs an MFMA slot of its own kind");
 
         // One K step t on slot `stage`.
         //   HEAD: the last HEADN copies of step t+1 are issued in sub-step 0
@@ -276,7 +278,7 @@ struct Pipeline {
         // (rows 16 KiB apart miss the L2 and the address translation caches far more often
         // than the MFMAs of half a step can hide); spreading them keeps every MFMA slot down
         // to one memory instruction, which is what a wave can issue in the shadow of one MFMA.
-        auto k_step = [&](auto head_c, auto tail_c, auto last_c, int t, int stage, int next) {
+        auto k_step = [&](auto head_c, auto tail_c, auto last_c, int t, int stage, int next) __attribute__((always_inline)) {
             constexpr bool HEAD = decltype(head_c)::value;
             constexpr bool TAIL = decltype(tail_c)::value;
             constexpr bool LAST = decltype(last_c)::value;
@@ -286,14 +288,8 @@ struct Pipeline {
                 if (ks + 1 < KSUB) {
 #pragma unroll
                     for (int m = 0; m < NM; ++m) {
-#pragma unroll
-                        for (int r = 0; r < NR; ++r)
-                            if (read_slot(r) == m) read(r, nxt, stage, ks + 1);
-                        if (HEAD && ks == 0) {
-#pragma unroll
-                            for (int c = TAILN; c < COPIES; ++c)
-                                if (copy_slot(c - TAILN) == m) copy(c, t + 1, next);
-                        }
+                        if (m % 2 == 0 && m / 2 < NR) read(m / 2, nxt, stage, ks + 1);
+                        if (HEAD && ks == 0 && m % 2 == 1 && m / 2 < HEADN) copy(TAILN + m / 2, t + 1, next);
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -306,14 +302,8 @@ struct Pipeline {
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int m = 0; m < NM; ++m) {
-#pragma unroll
-                        for (int r = 0; r < NR; ++r)
-                            if (read_slot(r) == m) read(r, nxt, next, 0);
-                        if (TAIL) {
-#pragma unroll
-                            for (int c = 0; c < TAILN; ++c)
-                                if (tail_slot(c) == m) copy(c, t + 2, stage);
-                        }
+                        if (m % 2 == 0 && m / 2 < NR) read(m / 2, nxt, next, 0);
+                        if (TAIL && m % TAIL_SPACING == 1 && m / TAIL_SPACING < TAILN) copy(m / TAIL_SPACING, t + 2, stage);
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -409,7 +399,8 @@ struct PersistentPipe {
     static constexpr int LDS_BYTES = PATCH_BASE + NW * PATCH_BYTES;
     static constexpr int COPY_ROWS = 8, A_COPIES = BM / COPY_ROWS / NW, COPIES = 2 * A_COPIES;
     static constexpr int TAILN = COPIES - HEADN;
-    static_assert(HEADN >= 1 && HEADN <= COPIES && 4 * TAILN <= MT * NT, "one memory instruction per MFMA slot");
+    static_assert(HEADN >= 0 && HEADN <= COPIES && 4 * (TAILN - 1) + 1 < MT * NT && 2 * (MT + NT) <= MT * NT,
+                  "every memory instruction of a group needs an MFMA slot of its own kind");
     static_assert(LDS_BYTES <= 163840 && KSUB == 2 && BM == BN, "written for the 256x256x64 tile");
 
     using tile_t = wave::Tile<T, MT, NT>;
@@ -440,7 +431,7 @@ struct PersistentPipe {
         const int a_row0 = (wave / WAVES_N) * WTM, b_row0 = (wave % WAVES_N) * WTN;
 
         // per-lane copy offsets for a tile (rows beyond the matrix re-read the last row)
-        auto set_offsets = [&](const Source& s) {
+        auto set_offsets = [&](const Source& s) __attribute__((always_inline)) {
             const int sub_row = lane / L::kChunksPerRow;
             const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
 #pragma unroll
@@ -453,24 +444,22 @@ struct PersistentPipe {
             }
         };
         // copy number c of the K step whose operands start at a_src / b_src, into slot `stage`
-        auto copy = [&](int c, const char* a_src, const char* b_src, int stage) {
+        auto copy = [&](int c, const char* a_src, const char* b_src, int stage) __attribute__((always_inline)) {
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
             if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], slot + c * NW * 1024);
             else copy_async_16(wv, b_src, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
         };
-        auto read = [&](int r, int buf, int stage, int ksub) {
+        auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES;
             if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
             else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
             else fa[buf][r - NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
         };
-        auto mfma = [&](int m, int buf) {
+        auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
             const int i = m / NT, j = m % NT;
             acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
         };
-        auto read_slot = [](int r) constexpr { return 2 * r; };
-        auto copy_slot = [](int c) constexpr { return 2 * c + 1; };
-        auto tail_slot = [](int c) constexpr { return 4 * c + 1; };
+        constexpr int TAIL_SPACING = 4;  // read r on slot 2r, head copy c on 2c+1, tail copy c on 4c+1
 
         // One K step computing from slot `stage`.  After the hand-over (wait, barrier, first
         // fragments of the next step) this slot is free, and sub-step 1 issues the first TAILN
@@ -480,16 +469,12 @@ struct PersistentPipe {
         // tile, so the loop never drains; switch_now loads that tile's copy offsets between
         // the two halves.
         auto k_step = [&](int stage, const char* a1, const char* b1, bool switch_now, const Source& to,
-                          const char* a2, const char* b2) {
+                          const char* a2, const char* b2) __attribute__((always_inline)) {
             const int next = stage ^ 1;
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
-#pragma unroll
-                for (int r = 0; r < NR; ++r)
-                    if (read_slot(r) == m) read(r, 1, stage, 1);
-#pragma unroll
-                for (int c = TAILN; c < COPIES; ++c)
-                    if (copy_slot(c - TAILN) == m) copy(c, a1, b1, next);
+                if (m % 2 == 0 && m / 2 < NR) read(m / 2, 1, stage, 1);
+                if (m % 2 == 1 && m / 2 < HEADN) copy(TAILN + m / 2, a1, b1, next);
                 mfma(m, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -500,12 +485,8 @@ struct PersistentPipe {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
-#pragma unroll
-                for (int r = 0; r < NR; ++r)
-                    if (read_slot(r) == m) read(r, 0, next, 0);
-#pragma unroll
-                for (int c = 0; c < TAILN; ++c)
-                    if (tail_slot(c) == m) copy(c, a2, b2, stage);
+                if (m % 2 == 0 && m / 2 < NR) read(m / 2, 0, next, 0);
+                if (m % TAIL_SPACING == 1 && m / TAIL_SPACING < TAILN) copy(m / TAIL_SPACING, a2, b2, stage);
                 mfma(m, 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -513,7 +494,7 @@ struct PersistentPipe {
         constexpr int STEP = L::kRowBytes;  // bytes one K step advances in a row
         // Keeps every accumulator block in the accumulation registers at the edges of the K
         // loop, so that the register allocator does not rotate blocks through VGPRs inside it.
-        auto pin_acc = [&]() {
+        auto pin_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -697,7 +678,7 @@ struct Staged {
         const bool all_regular = is_regular(a_sm, a_sk, a_vec) && is_regular(b_sn, b_sk, b_vec);
         const Regular pa = regular(a_sm, a_sk, a_rows, tid), pb = regular(b_sn, b_sk, b_rows, tid);
         u32x4 ra[CHUNKS], rb[CHUNKS];
-        auto fetch = [&](int k0) {
+        auto fetch = [&](int k0) __attribute__((always_inline)) {
             if (all_regular && k0 + BK <= k_end) {
                 gather_regular(ra, a_tile + ES * k0 * a_sk, a_sk, pa);
                 gather_regular(rb, b_tile + ES * k0 * b_sk, b_sk, pb);
