@@ -382,3 +382,35 @@ def test_error_codes_do_not_launch():
     assert P.prism_gemm(d, 64, 64, 64, x, 64, y, 64, x, 64) == P.Status.INVALID_ARG   # C aliases A
     d2 = P.make_desc(split_k=4)
     assert P.prism_gemm(d2, 64, 64, 512, x, 512, y, 512, z, 64) == P.Status.WORKSPACE
+
+
+# ---- seeded sweep over shapes, layouts, types and scalars -----------------------------------
+
+def _sweep_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        ab = ["bf16", "f16", "f32"][int(rng.integers(0, 3))]
+        cd = "f32" if ab == "f32" else ["bf16", "f16", "f32"][int(rng.integers(0, 3))]
+        aligned = bool(rng.integers(0, 2))
+        if aligned:   # shapes the fast pipeline takes (for 16-bit operands)
+            M, N, K = int(rng.integers(1, 9)) * 64, int(rng.integers(1, 9)) * 64, int(rng.integers(1, 9)) * 64
+            la, lb = "row", "col"
+            pad = (0, 0, 0)
+        else:
+            M, N, K = int(rng.integers(1, 400)), int(rng.integers(1, 400)), int(rng.integers(1, 300))
+            la, lb = ["row", "col"][int(rng.integers(0, 2))], ["row", "col"][int(rng.integers(0, 2))]
+            pad = tuple(int(v) for v in rng.integers(0, 9, size=3))
+        lc = ["row", "col"][int(rng.integers(0, 4) == 0)]
+        cases.append(dict(M=M, N=N, K=K, ab=ab, cd=cd, la=la, lb=lb, lc=lc, pad=pad,
+                          alpha=[1.0, -0.5, 2.0][int(rng.integers(0, 3))],
+                          beta=[0.0, 0.0, 0.75][int(rng.integers(0, 3))],
+                          bias=bool(rng.integers(0, 2)), batch=[1, 1, 3][int(rng.integers(0, 3))],
+                          split_k=[0, 0, 2][int(rng.integers(0, 3))], seed=100 + i))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(40, 2024), ids=lambda c: f"{c['M']}x{c['N']}x{c['K']}-{c['ab']}-{c['cd']}-{c['la'][0]}{c['lb'][0]}{c['lc'][0]}-b{c['batch']}-s{c['split_k']}")
+def test_seeded_sweep(case):
+    c = dict(case)
+    _general_case(c.pop("M"), c.pop("N"), c.pop("K"), **c)

@@ -102,3 +102,13 @@ def test_bounded_wait_gives_up_cleanly(monkeypatch):
     ok = bool((out.cpu().numpy().view(np.uint32) == inclusive_scan_u32_ref(x)).all())
     assert status in (0, int(P.Status.LAUNCH))
     assert ok or status == int(P.Status.LAUNCH)
+
+
+def test_seeded_sweep_of_sizes_offsets_and_modes():
+    rng = np.random.default_rng(99)
+    for i in range(25):
+        n = int(rng.integers(1, 6 * TILE))
+        offset = int(rng.integers(0, 4))
+        x = scan_input_u32(1000 + i, n)
+        got = _run(x, in_place=bool(rng.integers(0, 2)), offset=offset)
+        assert (got == inclusive_scan_u32_ref(x)).all(), (n, offset)
