@@ -17,6 +17,8 @@ using prism::GemmParams;
 constexpr int kComputeUnits = 256;
 constexpr int kPersistentMaxSteps = 16;  // longest K loop (in K steps) the persistent kernel is chosen for
 constexpr int kMaxSplit = 64;
+constexpr int kVeryLongK = 512;              // K steps from which few 256x256 tiles with many slices beat small tiles
+constexpr int kMinSliceStepsStaged = 8;      // shortest K loop (in K steps) a slice of the staged kernel gets
 constexpr int64_t kIntMax = 2147483647;
 
 struct Problem {
@@ -159,9 +161,13 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         plan.kernel = 2;
         int cfg = forced_pipe_config();
         if (cfg < 0) {
-            // Big tiles when they still give most compute units a workgroup, else small ones.
+            // Big tiles when they give at least half of the compute units a workgroup, or for a
+            // very long K (the split then needs fewer slices); else small tiles, two workgroups
+            // per compute unit.  Measured: 128x128 tiles win on square problems up to 2560^3
+            // (2048^3: 26 against 40 us) and on 1024x1024x8192 (30 against 38 us), 256x256 tiles
+            // from 3072^3 on and on 1024x1024x32768.
             const int64_t big = ceil_div(p.M, 256) * ceil_div(p.N, 256) * batch;
-            cfg = (big >= kComputeUnits / 2 || (p.M >= 512 && p.N >= 512)) ? 0 : 1;
+            cfg = (big >= kComputeUnits / 2 || ksteps >= kVeryLongK) ? 0 : 1;
         }
         out->pipe_config = cfg;
         tile_m = prism::kPipeConfigs[cfg].tile_m;
@@ -177,9 +183,19 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     const size_t slab_bytes = static_cast<size_t>(batch) * p.M * p.N * sizeof(float);
     if (want == 0) {
         want = 1;
-        if (units * 2 <= kComputeUnits && ksteps >= 8) {
-            want = kComputeUnits / units;
-            if (want > ksteps / 4) want = ksteps / 4;  // at least four K steps per slice
+        // A split costs a round trip of fp32 partial sums and a second kernel: it pays only for
+        // a long K loop, and every slice must keep a K loop of its own.  Small tiles run two
+        // workgroups per compute unit, so they are split until there are about twice as many
+        // workgroups as compute units (measured: 512x512x16384 23 us with 16 slices, 28 with
+        // 8 or 32).
+        const bool small_tiles = plan.kernel != 2 || out->pipe_config != 0;
+        const int64_t slots = small_tiles ? 2 * kComputeUnits : kComputeUnits;
+        const int64_t min_slice = plan.kernel != 2 ? kMinSliceStepsStaged : (small_tiles ? 16 : 32);
+        const int64_t min_k = plan.kernel != 2 ? 4 * kMinSliceStepsStaged : 64;
+        if (units * 2 <= slots && ksteps >= min_k) {
+            want = slots / units;
+            if (want > ksteps / min_slice) want = ksteps / min_slice;
+            if (small_tiles && want > 32) want = 32;
             if (want > kMaxSplit) want = kMaxSplit;
             if (want < 1) want = 1;
         }

@@ -278,6 +278,7 @@ def test_persistent_kernel_forced(M, N, K, batch, split, monkeypatch):
     """The persistent variant of the pipeline on small problems (one tile per workgroup, ragged
     edges, split K, batches, a few more tiles than compute units)."""
     monkeypatch.setenv("PRISM_PERSISTENT", "1")
+    monkeypatch.setenv("PRISM_GEMM_CONFIG", "0")        # the persistent kernel walks 256x256 tiles
     desc = P.make_desc(c_dtype="f32")
     s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, M * K, None, K, K * N, None, N, M * N, batch)
     assert s == 0 and plan.kernel == 3 and plan.workgroups <= 256
