@@ -57,16 +57,18 @@ __device__ __forceinline__ void barrier(persp::Workgroup) { __builtin_amdgcn_s_b
 __device__ __forceinline__ void sync(persp::Workgroup) { __syncthreads(); }
 
 // One wave-wide copy of 64 x 16 bytes from global memory straight into LDS: lane l's bytes
-// land at lds_addr + 16*l.  Wave-level: base and LDS address are per-wave values.
+// land at lds_base + lds_offset + 16*l.  Wave-level: base and LDS address are per-wave
+// values; lds_offset must be a compile-time constant at the point of use, so that a copy
+// costs two instructions (the LDS address goes to M0 with one scalar add).
 __device__ __forceinline__ void copy_async_16(persp::Wave, const char* uniform_base, uint32_t lane_offset,
-                                              uint32_t lds_addr)
+                                              uint32_t lds_base, int lds_offset)
 {
     uniform_base = scalarize(uniform_base);  // no-ops when the values already live in SGPRs
-    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_addr)
-                 : "memory");
+                 : "v"(lane_offset), "s"(uniform_base), "s"(lds_base), "i"(lds_offset)
+                 : "memory", "scc");
 }
 
 // Drains one wave's accumulator tile through a private LDS patch so that the
@@ -224,8 +226,8 @@ struct Pipeline {
         auto copy = [&](int c, int step, int stage) __attribute__((always_inline)) {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(wv, a_tile + k_bytes, g_off[c], slot + c * NW * 1024);
-            else copy_async_16(wv, b_tile + k_bytes, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
+            if (c < A_COPIES) copy_async_16(wv, a_tile + k_bytes, g_off[c], slot, c * NW * 1024);
+            else copy_async_16(wv, b_tile + k_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
         };
 
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
@@ -290,6 +292,7 @@ struct Pipeline {
                     for (int m = 0; m < NM; ++m) {
                         if (m % 2 == 0 && m / 2 < NR) read(m / 2, nxt, stage, ks + 1);
                         if (HEAD && ks == 0 && m % 2 == 1 && m / 2 < HEADN) copy(TAILN + m / 2, t + 1, next);
+                        __builtin_amdgcn_sched_barrier(0);  // memory instructions stay in front of their MFMA
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -304,6 +307,7 @@ struct Pipeline {
                     for (int m = 0; m < NM; ++m) {
                         if (m % 2 == 0 && m / 2 < NR) read(m / 2, nxt, next, 0);
                         if (TAIL && m % TAIL_SPACING == 1 && m / TAIL_SPACING < TAILN) copy(m / TAIL_SPACING, t + 2, stage);
+                        __builtin_amdgcn_sched_barrier(0);  // memory instructions stay in front of their MFMA
                         mfma(m, cur);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -327,7 +331,16 @@ struct Pipeline {
         }
         if (ksteps > 2) k_step(no{}, yes{}, no{}, 0, 0, 1);
         else k_step(no{}, no{}, no{}, 0, 0, 1);
-        for (t = 1; t + 2 < ksteps; ++t) k_step(yes{}, yes{}, no{}, t, t & 1, (t & 1) ^ 1);
+        // steady state, two steps per trip so that the slot of a step is a compile-time constant
+        // (LDS addresses fold into instruction offsets instead of being recomputed every step)
+        for (t = 1; t + 3 < ksteps; t += 2) {
+            k_step(yes{}, yes{}, no{}, t, 1, 0);
+            k_step(yes{}, yes{}, no{}, t + 1, 0, 1);
+        }
+        if (t + 2 < ksteps) {  // t is odd here
+            k_step(yes{}, yes{}, no{}, t, 1, 0);
+            ++t;
+        }
         if (t + 1 < ksteps) {  // t == ksteps - 2 >= 1: step t+1 >= 2 still needs its second half
             k_step(yes{}, no{}, no{}, t, t & 1, (t & 1) ^ 1);
             ++t;
@@ -446,8 +459,8 @@ struct PersistentPipe {
         // copy number c of the K step whose operands start at a_src / b_src, into slot `stage`
         auto copy = [&](int c, const char* a_src, const char* b_src, int stage) __attribute__((always_inline)) {
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], slot + c * NW * 1024);
-            else copy_async_16(wv, b_src, g_off[c], slot + A_BYTES + (c - A_COPIES) * NW * 1024);
+            if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], slot, c * NW * 1024);
+            else copy_async_16(wv, b_src, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
         };
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES;
@@ -475,6 +488,7 @@ struct PersistentPipe {
             for (int m = 0; m < NM; ++m) {
                 if (m % 2 == 0 && m / 2 < NR) read(m / 2, 1, stage, 1);
                 if (m % 2 == 1 && m / 2 < HEADN) copy(TAILN + m / 2, a1, b1, next);
+                __builtin_amdgcn_sched_barrier(0);
                 mfma(m, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -487,6 +501,7 @@ struct PersistentPipe {
             for (int m = 0; m < NM; ++m) {
                 if (m % 2 == 0 && m / 2 < NR) read(m / 2, 0, next, 0);
                 if (m % TAIL_SPACING == 1 && m / TAIL_SPACING < TAILN) copy(m / TAIL_SPACING, a2, b2, stage);
+                __builtin_amdgcn_sched_barrier(0);
                 mfma(m, 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
