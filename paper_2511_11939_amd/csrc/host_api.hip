@@ -229,7 +229,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         const char* e = std::getenv("PRISM_PERSISTENT");  // experiment hook: 0 = never, 1 = whenever possible
         const bool never = e && e[0] == '0', always = e && e[0] == '1';
         const int64_t last_slice_steps = ksteps - (split - 1) * slice_steps;
-        const bool possible = plan.kernel == 2 && out->pipe_config == 0 && slice_steps >= 2 && last_slice_steps >= 2;
+        const bool possible = plan.kernel == 2 && out->pipe_config == 0 && slice_steps >= 2 && last_slice_steps >= 2 &&
+                              slice_steps % 2 == 0 && last_slice_steps % 2 == 0;  // it walks K two steps at a time
         const bool pays = units * split > kComputeUnits && slice_steps <= kPersistentMaxSteps;
         if (possible && !never && (always || pays)) {
             plan.kernel = 3;

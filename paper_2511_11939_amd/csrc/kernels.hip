@@ -122,8 +122,8 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
 }
 
 // Persistent form for the 256x256x64 tile: workgroup w takes tiles w, w + gridDim.x, ...
-// and streams their K steps through wg::PersistentPipe.  Every unit must have at least
-// two K steps (the host guarantees it).
+// and streams their K steps through wg::PersistentPipe.  Every unit must have an even number
+// of K steps, at least two (the host guarantees it).
 template <typename T>
 __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const int total)
 {

@@ -428,7 +428,7 @@ struct PersistentPipe {
     };
 
     // Walks the tiles of one workgroup.
-    //   first / first_ksteps: operands and K steps (>= 2) of the first tile
+    //   first / first_ksteps: operands and K steps (even, >= 2) of the first tile
     //   peek(Source&, int& ksteps) -> bool: describes the tile after the current one, false if none
     //   finish(tile_t&): epilogue of the current tile (its accumulators are complete)
     //   advance(): the tile described by the last peek becomes the current one
@@ -481,9 +481,9 @@ struct PersistentPipe {
         // slot).  "Next" steps past the end of a tile are the first steps of the following
         // tile, so the loop never drains; switch_now loads that tile's copy offsets between
         // the two halves.
-        auto k_step = [&](int stage, const char* a1, const char* b1, bool switch_now, const Source& to,
+        auto k_step = [&](auto stage_c, const char* a1, const char* b1, bool switch_now, const Source& to,
                           const char* a2, const char* b2) __attribute__((always_inline)) {
-            const int next = stage ^ 1;
+            constexpr int stage = decltype(stage_c)::value, next = stage ^ 1;
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
                 if (m % 2 == 0 && m / 2 < NR) read(m / 2, 1, stage, 1);
@@ -530,7 +530,8 @@ struct PersistentPipe {
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
 
-        int stage = 0;
+        using slot0 = std::integral_constant<int, 0>;
+        using slot1 = std::integral_constant<int, 1>;
         for (;;) {
             // Without a following tile the copies past the end re-read this tile's first two
             // steps into slots nobody reads again: no branch around any copy.
@@ -539,14 +540,17 @@ struct PersistentPipe {
             const bool has_next = peek(sn, next_ksteps);
             acc.clear();
             pin_acc();
-            for (int t = 0; t < ksteps; ++t) {
-                const int t1 = t + 1, t2 = t + 2;
-                const char* a1 = t1 < ksteps ? sc.a + static_cast<int64_t>(t1) * STEP : sn.a;
-                const char* b1 = t1 < ksteps ? sc.b + static_cast<int64_t>(t1) * STEP : sn.b;
-                const char* a2 = t2 < ksteps ? sc.a + static_cast<int64_t>(t2) * STEP : sn.a + static_cast<int64_t>(t2 - ksteps) * STEP;
-                const char* b2 = t2 < ksteps ? sc.b + static_cast<int64_t>(t2) * STEP : sn.b + static_cast<int64_t>(t2 - ksteps) * STEP;
-                k_step(stage, a1, b1, t2 == ksteps, sn, a2, b2);
-                stage ^= 1;
+            // Every tile has an even number of K steps, so a trip of two steps always starts on
+            // slot 0 and slots are compile-time constants.  Past the end of the tile the copies
+            // continue with the first two steps of the next one.
+            for (int t = 0; t < ksteps; t += 2) {
+                const bool last = t + 2 == ksteps;
+                const char* a1 = sc.a + static_cast<int64_t>(t + 1) * STEP;
+                const char* b1 = sc.b + static_cast<int64_t>(t + 1) * STEP;
+                const char* a2 = last ? sn.a : sc.a + static_cast<int64_t>(t + 2) * STEP;
+                const char* b2 = last ? sn.b : sc.b + static_cast<int64_t>(t + 2) * STEP;
+                k_step(slot0{}, a1, b1, last, sn, a2, b2);
+                k_step(slot1{}, a2, b2, false, sn, a2 + STEP, b2 + STEP);
             }
             pin_acc();
             finish(acc);

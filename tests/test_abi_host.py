@@ -218,3 +218,10 @@ def test_scan_host_validation():
     assert P.prism_scan_u32(IN, OUT, 100, WS + 4, 1 << 20, None) == S.INVALID_ARG     # workspace alignment
     assert P.prism_scan_u32(IN, OUT, 100, IN + 64, 1 << 20, None) == S.INVALID_ARG    # workspace inside the data
     assert P.prism_scan_check(None, None) == S.INVALID_ARG
+
+
+def test_persistent_kernel_needs_an_even_number_of_k_steps():
+    d = P.make_desc()
+    even = _plan(d, 512, 512, 512, batch=256)
+    odd = _plan(d, 512, 512, 448, batch=256)           # 7 K steps
+    assert even.kernel == 3 and odd.kernel == 2 and odd.workgroups == 1024

@@ -272,7 +272,7 @@ def test_pipeline_short_k_loops(ksteps, monkeypatch):
         _general_case(256, 256, 64 * ksteps, ints=True)
 
 
-@pytest.mark.parametrize("M,N,K,batch,split", [(512, 768, 128, 1, 0), (520, 600, 192, 1, 0), (1024, 2304, 448, 1, 0),
+@pytest.mark.parametrize("M,N,K,batch,split", [(512, 768, 128, 1, 0), (520, 600, 256, 1, 0), (1024, 2304, 512, 1, 0),
                                                (512, 512, 1024, 1, 3), (512, 512, 256, 40, 0), (4352, 4352, 128, 1, 0)])
 def test_persistent_kernel_forced(M, N, K, batch, split, monkeypatch):
     """The persistent variant of the pipeline on small problems (one tile per workgroup, ragged
