@@ -153,13 +153,17 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     // ---- kernel and tile shape
     const int64_t step_k = 128 / ab_esize;  // a K step is 128 bytes of every operand row
     const int64_t ksteps = ceil_div(K, step_k);
-    const bool pipe_ok = ab_esize == 2 && p.a_vec && p.b_vec && K % 64 == 0 && p.a_sm < (int64_t{1} << 21) &&
-                         p.b_sn < (int64_t{1} << 21);
+    const bool pitch_ok = p.a_sm < (int64_t{1} << 21) && p.b_sn < (int64_t{1} << 21) && p.b_sk < (int64_t{1} << 21);
+    // B contiguous along n (a row-major B): whole, aligned 16-byte chunks of every k-row
+    const bool b_along_n = p.b_sn == 1 && p.b_sk != 1 && aligned(p.B, 16) && p.b_sk % 8 == 0 && p.N % 8 == 0 &&
+                           (p.batch == 1 || p.batch_b % 8 == 0);
+    const bool pipe_ok = ab_esize == 2 && p.a_vec && (p.b_vec || b_along_n) && K % 64 == 0 && pitch_ok;
     int tile_m = prism::kStagedTileM, tile_n = prism::kStagedTileN, waves = prism::kStagedWaves;
     plan.kernel = 1;
     if (pipe_ok) {
         plan.kernel = 2;
         int cfg = forced_pipe_config();
+        if (cfg > 1) cfg = -1;  // the hook names a tile size (0: 256x256, 1: 128x128)
         if (cfg < 0) {
             // Big tiles when they give at least half of the compute units a workgroup, or for a
             // very long K (the split then needs fewer slices); else small tiles, two workgroups
@@ -169,6 +173,7 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
             const int64_t big = ceil_div(p.M, 256) * ceil_div(p.N, 256) * batch;
             cfg = (big >= kComputeUnits / 2 || ksteps >= kVeryLongK) ? 0 : 1;
         }
+        if (!p.b_vec) cfg = 2;  // B contiguous along n: 128x128 tiles, B kept as k-rows in LDS
         out->pipe_config = cfg;
         tile_m = prism::kPipeConfigs[cfg].tile_m;
         tile_n = prism::kPipeConfigs[cfg].tile_n;

@@ -156,11 +156,19 @@ __device__ __forceinline__ void drain_runs(persp::Wave, const TileT& acc, char* 
 }
 
 // ------------------------------------------------------------------------------------
-// Pipelined main loop: K-contiguous operands, direct-to-LDS copies, STAGES slots.
+// Pipelined main loop: direct-to-LDS copies, STAGES slots.  A is K-contiguous.  B is
+// K-contiguous too (B_KN false: its LDS tile is BN rows of BK elements, like A's) or
+// contiguous along n (B_KN true: its LDS tile is BK k-rows of BN elements, copied as it
+// lies in memory; the fragments, which need consecutive k per lane, are fetched with the
+// transposing LDS read of gfx950, two per fragment).
 // ------------------------------------------------------------------------------------
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, bool B_KN = false>
 struct Pipeline {
     using L = lane::TileLayout<BK>;
+    // (With 256x256 tiles the extra fragment addresses of this variant do not fit beside the
+    // accumulators: it was built, spilled several hundred registers and ran at half the speed
+    // of the 128x128 form, which is the one kept.)
+    static_assert(!B_KN || (BK == 64 && BN == 128), "n-contiguous B: 64 k-rows of 128 elements");
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -202,7 +210,8 @@ struct Pipeline {
     {
         const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
         constexpr int NM = MT * NT;   // MFMAs per sub-step
-        constexpr int NR = MT + NT;   // fragment reads per sub-step
+        constexpr int B_READS = B_KN ? 2 : 1;      // LDS reads per B fragment
+        constexpr int NR = MT + B_READS * NT;      // fragment reads per sub-step
         // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave) of COPY_ROWS rows;
         //    a lane fills one chunk position of one row with the logical chunk the swizzle wants.
         const int sub_row = lane / L::kChunksPerRow;
@@ -214,36 +223,73 @@ struct Pipeline {
             row = row < a_rows ? row : a_rows - 1;
             g_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
         }
+        // n-contiguous B: a k-row of the tile is BN*2 bytes; a wave-wide copy moves KN_ROWS of
+        // them.  The 16-byte chunk c of k-row k sits at position c ^ 2*(k%4), so that the four
+        // k-rows a transposing read touches fall on four different 32-byte bank groups.
+        constexpr int KN_ROW_BYTES = BN * 2, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
 #pragma unroll
         for (int i = 0; i < B_COPIES; ++i) {
-            int row = (i * NW + wave) * COPY_ROWS + sub_row;
-            row = row < b_rows ? row : b_rows - 1;
-            g_off[A_COPIES + i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
+            if constexpr (!B_KN) {
+                int row = (i * NW + wave) * COPY_ROWS + sub_row;
+                row = row < b_rows ? row : b_rows - 1;
+                g_off[A_COPIES + i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
+            } else {
+                // b_rows counts the columns of the tile that exist (a multiple of 8); chunks
+                // beyond them re-read the last one that exists and only feed columns never stored
+                const int k_row = (i * NW + wave) * KN_ROWS + lane / KN_CHUNKS;
+                int c = (lane % KN_CHUNKS) ^ ((k_row & 3) << 1);
+                const int last = (b_rows - 1) / 8;
+                c = c < last ? c : last;
+                g_off[A_COPIES + i] = static_cast<uint32_t>(k_row) * b_ld + c * lane::kChunkBytes;
+            }
         }
         const uint32_t lds0 = lds_address(lds) + wave * 1024;
 
         // copy number c (0 .. COPIES-1) of K step `step` into slot `stage`
         auto copy = [&](int c, int step, int stage) __attribute__((always_inline)) {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
+            const int64_t b_bytes = B_KN ? static_cast<int64_t>(step) * BK * b_ld : k_bytes;
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
             if (c < A_COPIES) copy_async_16(wv, a_tile + k_bytes, g_off[c], slot, c * NW * 1024);
-            else copy_async_16(wv, b_tile + k_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
+            else copy_async_16(wv, b_tile + b_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
+        };
+        // Half h (4 consecutive k) of fragment j of an n-contiguous B.  The 16 lanes of a group
+        // point at 4 k-rows x 16 n (lane i: k-row i/4, n-quad i%4); the transposing read hands
+        // lane i the four k of column n0 + i.
+        auto read_b_kn = [&](int j, int stage, int ksub, int h) __attribute__((always_inline)) {
+            using v4s = __attribute__((ext_vector_type(4))) short;
+            const int i = lane & 15, kq = lane >> 4;
+            const int n = (wave % WAVES_N) * WTN + lane::kBlock * j + 4 * (i & 3);
+            const int k_row = 32 * ksub + 8 * kq + 4 * h + (i >> 2);
+            const char* src = lds + stage * STAGE_BYTES + A_BYTES + k_row * KN_ROW_BYTES +
+                              (((n >> 3) ^ ((i >> 2) << 1)) * lane::kChunkBytes) + (n & 7) * 2;
+            return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4s*)src);
         };
 
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
+        using v4s = __attribute__((ext_vector_type(4))) short;
         frag_t fa[2][MT], fb[2][NT];
+        v4s fbh[2][NT][2];  // n-contiguous B only: the two halves of every fragment
         // read number r (0 .. NR-1) of sub-step ksub of slot `stage` into buffer `buf`;
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES;
             if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
-            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
-            else fa[buf][r - NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
+            else if (r <= B_READS * NT) {
+                if constexpr (B_KN) fbh[buf][(r - 1) / 2][(r - 1) % 2] = read_b_kn((r - 1) / 2, stage, ksub, (r - 1) % 2);
+                else fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
+            } else fa[buf][r - B_READS * NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - B_READS * NT), ksub, lane);
         };
         auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
             const int i = m / NT, j = m % NT;
-            acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            if constexpr (B_KN) {
+                const auto b8 = __builtin_shufflevector(fbh[buf][j][0], fbh[buf][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                acc.acc[i][j] = wave::mfma_block(wv, __builtin_bit_cast(frag_t, b8), fa[buf][i], acc.acc[i][j]);
+            } else {
+                acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
+            }
         };
 
         // -- prologue: fill the slots, wait for step 0, fetch its first fragments
@@ -262,15 +308,16 @@ struct Pipeline {
 
         // MFMA slots of the memory instructions of a group: reads on the even slots, copies on
         // the odd ones, so no MFMA has more than one of them in its 16-cycle shadow.
-        // Read r sits on slot 2r, head copy c on slot 2c+1, tail copy c on slot
+        // Read r sits on slot READ_SPACING*r, head copy c on slot 2c+1, tail copy c on slot
         // TAIL_SPACING*c+1.  The first TAILN copies of a step are issued right after the slot
         // is released, the last HEADN at the start of the following step.  (The slot of an
         // instruction is computed from the slot index, not searched for: the loops below are
         // unrolled in full, and their size before unrolling is limited.)
         constexpr int HEADN = COPIES / 4, TAILN = COPIES - HEADN;
         constexpr int TAIL_SPACING = 4 * (TAILN - 1) + 1 < NM ? 4 : 2;
-        static_assert(2 * NR <= NM && 2 * HEADN <= NM && TAIL_SPACING * (TAILN - 1) + 1 < NM,
-                      "every memory instruction of a group needs an MFMA slot of its own kind");
+        constexpr int READ_SPACING = 2 * NR <= NM ? 2 : 1;  // reads share slots with copies only when they must
+        static_assert(NR <= NM && 2 * HEADN <= NM && TAIL_SPACING * (TAILN - 1) + 1 < NM,
+                      "every memory instruction of a group needs an MFMA slot");
 
         // One K step t on slot `stage`.
         //   HEAD: the last HEADN copies of step t+1 are issued in sub-step 0
@@ -290,7 +337,7 @@ struct Pipeline {
                 if (ks + 1 < KSUB) {
 #pragma unroll
                     for (int m = 0; m < NM; ++m) {
-                        if (m % 2 == 0 && m / 2 < NR) read(m / 2, nxt, stage, ks + 1);
+                        if (m % READ_SPACING == 0 && m / READ_SPACING < NR) read(m / READ_SPACING, nxt, stage, ks + 1);
                         if (HEAD && ks == 0 && m % 2 == 1 && m / 2 < HEADN) copy(TAILN + m / 2, t + 1, next);
                         __builtin_amdgcn_sched_barrier(0);  // memory instructions stay in front of their MFMA
                         mfma(m, cur);
@@ -305,7 +352,7 @@ struct Pipeline {
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int m = 0; m < NM; ++m) {
-                        if (m % 2 == 0 && m / 2 < NR) read(m / 2, nxt, next, 0);
+                        if (m % READ_SPACING == 0 && m / READ_SPACING < NR) read(m / READ_SPACING, nxt, next, 0);
                         if (TAIL && m % TAIL_SPACING == 1 && m / TAIL_SPACING < TAILN) copy(m / TAIL_SPACING, t + 2, stage);
                         __builtin_amdgcn_sched_barrier(0);  // memory instructions stay in front of their MFMA
                         mfma(m, cur);

@@ -110,7 +110,7 @@ def _plan(desc, M, N, K, batch=1, A=None, B=None, C=None, lda=None, ldb=None):
 
 def test_plans_for_the_five_workloads():
     p = _plan(P.make_desc(layout_b="row", c_dtype="f32"), 256, 256, 256)
-    assert p.kernel == 1 and p.split_k == 1                       # row-major B: staged kernel
+    assert p.kernel == 2 and p.tile_m == 128 and p.split_k == 1   # row-major B: pipeline, B kept as k-rows in LDS
     p = _plan(P.make_desc(), 4096, 4096, 4096)
     assert (p.kernel, p.tile_m, p.tile_n, p.tile_k, p.workgroups, p.split_k) == (2, 256, 256, 64, 256, 1)
     p = _plan(P.make_desc(), 16384, 4096, 4096)

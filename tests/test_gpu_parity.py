@@ -47,7 +47,7 @@ def test_cfg1_random_every_entry():
     w = CONFIGS["cfg1_256_rowrow_f32"]
     inp = make_inputs(w)
     c, plan = run_workload(w, inp)
-    assert plan["kernel"] == 1            # row-major B goes through the staged kernel
+    assert plan["kernel"] == 2 and plan["tile_m"] == 128      # row-major B: the pipeline with transposing LDS reads
     assert_matches_oracle(w, inp, c)
 
 
@@ -325,6 +325,20 @@ def test_sgemm_4096_workload_sampled_rows():
 def test_sgemm_square_1024_every_entry():
     """Row-major A, B and C as in the paper's sgemm study, several tiles in each direction."""
     _general_case(1024, 1024, 1024, ab="f32", la="row", lb="row", alpha=1.5, beta=0.5, seed=3)
+
+
+@pytest.mark.parametrize("M,N,K,batch,split", [(256, 256, 64, 1, 0), (512, 768, 256, 1, 0), (300, 520, 192, 1, 0),
+                                               (100, 88, 640, 1, 0), (384, 264, 512, 3, 0), (256, 512, 2048, 1, 4),
+                                               (1024, 1280, 320, 1, 0)])
+def test_row_major_b_on_the_pipeline(M, N, K, batch, split):
+    """B contiguous along n (row-major B) with aligned rows runs on the direct-to-LDS pipeline:
+    its tile stays k-rows in LDS and the fragments come from transposing reads."""
+    desc = P.make_desc(c_dtype="f32", layout_b="row")
+    s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, M * K, None, N, K * N, None, N, M * N, batch)
+    assert s == 0 and plan.kernel == 2 and plan.tile_m == 128
+    _general_case(M, N, K, lb="row", ints=True, batch=batch, split_k=split)
+    _general_case(M, N, K, lb="row", ab="f16", cd="bf16", bias=True, alpha=-1.25, batch=batch, split_k=split)
+    _general_case(M, N, K, lb="row", lc="col", pad=(8, 16, 8), batch=batch, split_k=split)   # col-major C: run transposed
 
 
 def test_unaligned_pointers_and_odd_ld():
