@@ -110,10 +110,11 @@ typedef struct prism_gemm_plan {
  *
  * M == 0 or N == 0: nothing is written, PRISM_OK.  K == 0: C <- bias + beta*C.
  * Any positive sizes, leading dimensions and alignments are accepted.  16-bit
- * operands with 16-byte aligned rows and K a multiple of 64 run on the fast
- * pipeline when A is contiguous along K and B is contiguous along K (column-
- * major B) or along n (row-major B, N a multiple of 8); everything else (fp32
- * operands included) runs on a staged kernel with the same arithmetic.  For a fixed problem, descriptor and GPU the result is
+ * operands in either layout run on the fast pipeline when their rows (or
+ * columns) start on 16-byte boundaries, K is a multiple of 64 and, for an
+ * operand that is not contiguous along K (column-major A, row-major B), M
+ * respectively N is a multiple of 8; everything else (fp32 operands included)
+ * runs on a staged kernel with the same arithmetic.  For a fixed problem, descriptor and GPU the result is
  * bit-for-bit reproducible: split-K partial sums are reduced in slice order.
  */
 PRISM_API prism_status_t prism_gemm(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,

@@ -157,7 +157,10 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     // B contiguous along n (a row-major B): whole, aligned 16-byte chunks of every k-row
     const bool b_along_n = p.b_sn == 1 && p.b_sk != 1 && aligned(p.B, 16) && p.b_sk % 8 == 0 && p.N % 8 == 0 &&
                            (p.batch == 1 || p.batch_b % 8 == 0);
-    const bool pipe_ok = ab_esize == 2 && p.a_vec && (p.b_vec || b_along_n) && K % 64 == 0 && pitch_ok;
+    const bool a_along_m = p.a_sm == 1 && p.a_sk != 1 && aligned(p.A, 16) && p.a_sk % 8 == 0 && p.M % 8 == 0 &&
+                           (p.batch == 1 || p.batch_a % 8 == 0);
+    const bool pipe_ok = ab_esize == 2 && (p.a_vec || a_along_m) && (p.b_vec || b_along_n) && K % 64 == 0 &&
+                         pitch_ok && p.a_sk < (int64_t{1} << 21);
     int tile_m = prism::kStagedTileM, tile_n = prism::kStagedTileN, waves = prism::kStagedWaves;
     plan.kernel = 1;
     if (pipe_ok) {
@@ -173,7 +176,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
             const int64_t big = ceil_div(p.M, 256) * ceil_div(p.N, 256) * batch;
             cfg = (big >= kComputeUnits / 2 || ksteps >= kVeryLongK) ? 0 : 1;
         }
-        if (!p.b_vec) cfg = 2;  // B contiguous along n: 128x128 tiles, B kept as k-rows in LDS
+        // an operand that is not K-contiguous: 128x128 tiles, that operand kept as k-rows in LDS
+        if (!p.a_vec || !p.b_vec) cfg = !p.a_vec ? (!p.b_vec ? 4 : 3) : 2;
         out->pipe_config = cfg;
         tile_m = prism::kPipeConfigs[cfg].tile_m;
         tile_n = prism::kPipeConfigs[cfg].tile_n;

@@ -17,6 +17,8 @@ const PipeConfig kPipeConfigs[kNumPipeConfigs] = {
     {0, 256, 256, 64, 4, 2, "256x256x64_w4"},
     {1, 128, 128, 64, 4, 2, "128x128x64_w4"},
     {2, 128, 128, 64, 4, 2, "128x128x64_w4_b_along_n"},
+    {3, 128, 128, 64, 4, 2, "128x128x64_w4_a_along_m"},
+    {4, 128, 128, 64, 4, 2, "128x128x64_w4_a_along_m_b_along_n"},
 };
 
 namespace {
@@ -108,16 +110,17 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Placement q = place<BM, BN>(p, blockIdx.x);
 
-    const char* a_tile = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm + q.k_begin);
+    const char* a_tile = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm + q.k_begin * p.a_sk);
     const char* b_tile = p.B + 2 * (q.batch * p.batch_b + q.n0 * p.b_sn + q.k_begin * p.b_sk);
     const int a_rows = p.M - q.m0 < BM ? p.M - q.m0 : BM;
     const int b_rows = p.N - q.n0 < BN ? p.N - q.n0 : BN;
-    // pitch of a row of B's LDS tile: an n-row (K-contiguous B) or a k-row (n-contiguous B)
+    // pitch of a row of an LDS tile: a row of the matrix (K-contiguous operand) or a k-row
+    const uint32_t a_ld = static_cast<uint32_t>(2 * (p.a_sk == 1 ? p.a_sm : p.a_sk));
     const uint32_t b_ld = static_cast<uint32_t>(2 * (p.b_sk == 1 ? p.b_sn : p.b_sk));
 
     typename P::tile_t acc;
     acc.clear();
-    P::run(wgp, acc, a_tile, static_cast<uint32_t>(2 * p.a_sm), a_rows, b_tile, b_ld, b_rows,
+    P::run(wgp, acc, a_tile, a_ld, a_rows, b_tile, b_ld, b_rows,
            (q.k_end - q.k_begin) / BK, lds, wave, lane);
 
     epilogue<typename P::tile_t, P::MT, P::NT>(wgp, p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
@@ -241,6 +244,8 @@ hipError_t launch_pipe_config(int config, const GemmParams& p, int workgroups, h
     case 0: return launch_pipe<wg::Pipeline<T, 256, 256, 64, 2, 2, 2>, 256, 256, 64, 2>(p, workgroups, stream);
     case 1: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2>, 128, 128, 64, 2>(p, workgroups, stream);
     case 2: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2, true>, 128, 128, 64, 2>(p, workgroups, stream);
+    case 3: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2, false, true>, 128, 128, 64, 2>(p, workgroups, stream);
+    case 4: return launch_pipe<wg::Pipeline<T, 128, 128, 64, 2, 2, 2, true, true>, 128, 128, 64, 2>(p, workgroups, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -13,7 +13,7 @@ struct PipeConfig {
     int tile_m, tile_n, tile_k, waves, stages;
     const char* name;
 };
-constexpr int kNumPipeConfigs = 3;  // 0, 1: both operands K-contiguous; 2: B contiguous along n
+constexpr int kNumPipeConfigs = 5;  // 0, 1: both operands K-contiguous; 2-4: B along n, A along m, both
 extern const PipeConfig kPipeConfigs[kNumPipeConfigs];
 
 constexpr int kStagedTileM = 128, kStagedTileN = 128, kStagedWaves = 4;

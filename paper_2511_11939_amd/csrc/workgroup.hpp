@@ -156,19 +156,20 @@ __device__ __forceinline__ void drain_runs(persp::Wave, const TileT& acc, char* 
 }
 
 // ------------------------------------------------------------------------------------
-// Pipelined main loop: direct-to-LDS copies, STAGES slots.  A is K-contiguous.  B is
-// K-contiguous too (B_KN false: its LDS tile is BN rows of BK elements, like A's) or
-// contiguous along n (B_KN true: its LDS tile is BK k-rows of BN elements, copied as it
-// lies in memory; the fragments, which need consecutive k per lane, are fetched with the
-// transposing LDS read of gfx950, two per fragment).
+// Pipelined main loop: direct-to-LDS copies, STAGES slots.  An operand is K-contiguous
+// (its LDS tile is BM or BN rows of BK elements) or contiguous along its other index
+// (A_MK: A along m, B_KN: B along n; the LDS tile is then BK k-rows of BM or BN elements,
+// copied as it lies in memory, and the fragments, which need consecutive k per lane, are
+// fetched with the transposing LDS read of gfx950, two per fragment).
 // ------------------------------------------------------------------------------------
-template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, bool B_KN = false>
+template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, bool B_KN = false, bool A_MK = false>
 struct Pipeline {
     using L = lane::TileLayout<BK>;
     // (With 256x256 tiles the extra fragment addresses of this variant do not fit beside the
     // accumulators: it was built, spilled several hundred registers and ran at half the speed
     // of the 128x128 form, which is the one kept.)
     static_assert(!B_KN || (BK == 64 && BN == 128), "n-contiguous B: 64 k-rows of 128 elements");
+    static_assert(!A_MK || (BK == 64 && BM == 128), "m-contiguous A: 64 k-rows of 128 elements");
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -210,23 +211,37 @@ struct Pipeline {
     {
         const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
         constexpr int NM = MT * NT;   // MFMAs per sub-step
-        constexpr int B_READS = B_KN ? 2 : 1;      // LDS reads per B fragment
-        constexpr int NR = MT + B_READS * NT;      // fragment reads per sub-step
+        constexpr int A_READS = A_MK ? 2 : 1, B_READS = B_KN ? 2 : 1;  // LDS reads per fragment
+        constexpr int NR = A_READS * MT + B_READS * NT;                // fragment reads per sub-step
         // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave) of COPY_ROWS rows;
         //    a lane fills one chunk position of one row with the logical chunk the swizzle wants.
         const int sub_row = lane / L::kChunksPerRow;
         const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
         uint32_t g_off[COPIES];
+        // An operand kept as k-rows: a k-row of the tile is 256 bytes (128 elements) and a
+        // wave-wide copy moves four of them.  The 16-byte chunk c of k-row k sits at position
+        // c ^ 2*(k%4), so that the four k-rows a transposing read touches fall on four different
+        // 32-byte bank groups.  `cols` counts the elements of a k-row that exist (a multiple of
+        // 8); chunks beyond them re-read the last one that exists and only feed results that
+        // are never stored.
+        constexpr int KN_ROW_BYTES = 256, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
+        auto k_row_offset = [&](int i, uint32_t ld, int cols) __attribute__((always_inline)) {
+            const int k_row = (i * NW + wave) * KN_ROWS + lane / KN_CHUNKS;
+            int c = (lane % KN_CHUNKS) ^ ((k_row & 3) << 1);
+            const int last = (cols - 1) / 8;
+            c = c < last ? c : last;
+            return static_cast<uint32_t>(k_row) * ld + c * lane::kChunkBytes;
+        };
 #pragma unroll
         for (int i = 0; i < A_COPIES; ++i) {
-            int row = (i * NW + wave) * COPY_ROWS + sub_row;
-            row = row < a_rows ? row : a_rows - 1;
-            g_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
+            if constexpr (!A_MK) {
+                int row = (i * NW + wave) * COPY_ROWS + sub_row;
+                row = row < a_rows ? row : a_rows - 1;
+                g_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
+            } else {
+                g_off[i] = k_row_offset(i, a_ld, a_rows);
+            }
         }
-        // n-contiguous B: a k-row of the tile is BN*2 bytes; a wave-wide copy moves KN_ROWS of
-        // them.  The 16-byte chunk c of k-row k sits at position c ^ 2*(k%4), so that the four
-        // k-rows a transposing read touches fall on four different 32-byte bank groups.
-        constexpr int KN_ROW_BYTES = BN * 2, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
 #pragma unroll
         for (int i = 0; i < B_COPIES; ++i) {
             if constexpr (!B_KN) {
@@ -234,13 +249,7 @@ struct Pipeline {
                 row = row < b_rows ? row : b_rows - 1;
                 g_off[A_COPIES + i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
             } else {
-                // b_rows counts the columns of the tile that exist (a multiple of 8); chunks
-                // beyond them re-read the last one that exists and only feed columns never stored
-                const int k_row = (i * NW + wave) * KN_ROWS + lane / KN_CHUNKS;
-                int c = (lane % KN_CHUNKS) ^ ((k_row & 3) << 1);
-                const int last = (b_rows - 1) / 8;
-                c = c < last ? c : last;
-                g_off[A_COPIES + i] = static_cast<uint32_t>(k_row) * b_ld + c * lane::kChunkBytes;
+                g_off[A_COPIES + i] = k_row_offset(i, b_ld, b_rows);
             }
         }
         const uint32_t lds0 = lds_address(lds) + wave * 1024;
@@ -248,48 +257,58 @@ struct Pipeline {
         // copy number c (0 .. COPIES-1) of K step `step` into slot `stage`
         auto copy = [&](int c, int step, int stage) __attribute__((always_inline)) {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
+            const int64_t a_bytes = A_MK ? static_cast<int64_t>(step) * BK * a_ld : k_bytes;
             const int64_t b_bytes = B_KN ? static_cast<int64_t>(step) * BK * b_ld : k_bytes;
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(wv, a_tile + k_bytes, g_off[c], slot, c * NW * 1024);
+            if (c < A_COPIES) copy_async_16(wv, a_tile + a_bytes, g_off[c], slot, c * NW * 1024);
             else copy_async_16(wv, b_tile + b_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
         };
-        // Half h (4 consecutive k) of fragment j of an n-contiguous B.  The 16 lanes of a group
-        // point at 4 k-rows x 16 n (lane i: k-row i/4, n-quad i%4); the transposing read hands
-        // lane i the four k of column n0 + i.
-        auto read_b_kn = [&](int j, int stage, int ksub, int h) __attribute__((always_inline)) {
+        // Half h (4 consecutive k) of the fragment whose 16 rows start at element `first` of
+        // the k-rows of the tile at `tile`.  The 16 lanes of a group point at 4 k-rows x 16
+        // elements (lane i: k-row i/4, quad i%4); the transposing read hands lane i the four k
+        // of element first + i.
+        auto read_k_rows = [&](const char* tile, int first, int ksub, int h) __attribute__((always_inline)) {
             using v4s = __attribute__((ext_vector_type(4))) short;
             const int i = lane & 15, kq = lane >> 4;
-            const int n = (wave % WAVES_N) * WTN + lane::kBlock * j + 4 * (i & 3);
+            const int n = first + 4 * (i & 3);
             const int k_row = 32 * ksub + 8 * kq + 4 * h + (i >> 2);
-            const char* src = lds + stage * STAGE_BYTES + A_BYTES + k_row * KN_ROW_BYTES +
-                              (((n >> 3) ^ ((i >> 2) << 1)) * lane::kChunkBytes) + (n & 7) * 2;
-            return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) v4s*)src);
+            const char* src = tile + k_row * KN_ROW_BYTES + (((n >> 3) ^ ((i >> 2) << 1)) * lane::kChunkBytes) + (n & 7) * 2;
+            return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)src);
         };
 
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
         using v4s = __attribute__((ext_vector_type(4))) short;
         frag_t fa[2][MT], fb[2][NT];
-        v4s fbh[2][NT][2];  // n-contiguous B only: the two halves of every fragment
+        v4s fah[2][MT][2], fbh[2][NT][2];  // operands kept as k-rows: the two halves of every fragment
         // read number r (0 .. NR-1) of sub-step ksub of slot `stage` into buffer `buf`;
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
-        auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
+        auto read_a = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {  // x: fragment * A_READS + half
             const char* st = lds + stage * STAGE_BYTES;
-            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
-            else if (r <= B_READS * NT) {
-                if constexpr (B_KN) fbh[buf][(r - 1) / 2][(r - 1) % 2] = read_b_kn((r - 1) / 2, stage, ksub, (r - 1) % 2);
-                else fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
-            } else fa[buf][r - B_READS * NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - B_READS * NT), ksub, lane);
+            if constexpr (A_MK) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            else fa[buf][x] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * x, ksub, lane);
+        };
+        auto read_b = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {
+            const char* st = lds + stage * STAGE_BYTES + A_BYTES;
+            if constexpr (B_KN) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            else fb[buf][x] = lane::load_fragment<T, BK>(wv.lane(), st, b_row0 + lane::kBlock * x, ksub, lane);
+        };
+        auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
+            if (r < A_READS) read_a(r, buf, stage, ksub);
+            else if (r < A_READS + B_READS * NT) read_b(r - A_READS, buf, stage, ksub);
+            else read_a(r - B_READS * NT, buf, stage, ksub);
+        };
+        auto whole = [](v4s lo, v4s hi) __attribute__((always_inline)) {
+            return __builtin_bit_cast(frag_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         };
         auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
             const int i = m / NT, j = m % NT;
-            if constexpr (B_KN) {
-                const auto b8 = __builtin_shufflevector(fbh[buf][j][0], fbh[buf][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
-                acc.acc[i][j] = wave::mfma_block(wv, __builtin_bit_cast(frag_t, b8), fa[buf][i], acc.acc[i][j]);
-            } else {
-                acc.acc[i][j] = wave::mfma_block(wv, fb[buf][j], fa[buf][i], acc.acc[i][j]);
-            }
+            frag_t a, b;
+            if constexpr (A_MK) a = whole(fah[buf][i][0], fah[buf][i][1]);
+            else a = fa[buf][i];
+            if constexpr (B_KN) b = whole(fbh[buf][j][0], fbh[buf][j][1]);
+            else b = fb[buf][j];
+            acc.acc[i][j] = wave::mfma_block(wv, b, a, acc.acc[i][j]);
         };
 
         // -- prologue: fill the slots, wait for step 0, fetch its first fragments

@@ -129,7 +129,12 @@ def test_plan_falls_back_to_staged_kernel():
     assert _plan(d, 256, 256, 100).kernel == 1                     # K not a multiple of 64
     assert _plan(d, 256, 256, 128, A=FAKE + 2).kernel == 1         # misaligned A
     assert _plan(d, 256, 256, 128, lda=129).kernel == 1            # rows not 16-byte aligned
-    assert _plan(P.make_desc(layout_a="col"), 256, 256, 128).kernel == 1
+    # operands contiguous along m or n stay on the pipeline when whole aligned chunks exist
+    pc = _plan(P.make_desc(layout_a="col"), 256, 256, 128)
+    assert pc.kernel == 2 and pc.tile_m == 128
+    assert _plan(P.make_desc(layout_a="col"), 252, 256, 128).kernel == 1                  # M not a multiple of 8
+    assert _plan(P.make_desc(layout_a="col", layout_b="row"), 256, 256, 128).kernel == 2
+    assert _plan(P.make_desc(layout_b="row"), 256, 260, 128).kernel == 1                   # N not a multiple of 8
     assert _plan(d, 256, 256, 128).kernel == 2
     # a column-major C is run as the transposed problem
     pc = _plan(P.make_desc(layout_c="col"), 320, 256, 128)

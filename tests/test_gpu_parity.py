@@ -330,15 +330,20 @@ def test_sgemm_square_1024_every_entry():
 @pytest.mark.parametrize("M,N,K,batch,split", [(256, 256, 64, 1, 0), (512, 768, 256, 1, 0), (300, 520, 192, 1, 0),
                                                (100, 88, 640, 1, 0), (384, 264, 512, 3, 0), (256, 512, 2048, 1, 4),
                                                (1024, 1280, 320, 1, 0)])
-def test_row_major_b_on_the_pipeline(M, N, K, batch, split):
-    """B contiguous along n (row-major B) with aligned rows runs on the direct-to-LDS pipeline:
-    its tile stays k-rows in LDS and the fragments come from transposing reads."""
-    desc = P.make_desc(c_dtype="f32", layout_b="row")
-    s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, M * K, None, N, K * N, None, N, M * N, batch)
+@pytest.mark.parametrize("la,lb", [("row", "row"), ("col", "col"), ("col", "row")])
+def test_operands_not_contiguous_along_k_on_the_pipeline(la, lb, M, N, K, batch, split):
+    """An operand contiguous along m or n (column-major A, row-major B) with aligned rows runs on
+    the direct-to-LDS pipeline: its tile stays k-rows in LDS and the fragments come from
+    transposing reads."""
+    if la == "col" and M % 8:
+        M += 8 - M % 8                                 # whole 16-byte chunks of every k-row of A
+    desc = P.make_desc(c_dtype="f32", layout_a=la, layout_b=lb)
+    lda, ldb = (K if la == "row" else M), (N if lb == "row" else K)
+    s, plan = P.prism_gemm_plan(desc, M, N, K, None, lda, M * K, None, ldb, K * N, None, N, M * N, batch)
     assert s == 0 and plan.kernel == 2 and plan.tile_m == 128
-    _general_case(M, N, K, lb="row", ints=True, batch=batch, split_k=split)
-    _general_case(M, N, K, lb="row", ab="f16", cd="bf16", bias=True, alpha=-1.25, batch=batch, split_k=split)
-    _general_case(M, N, K, lb="row", lc="col", pad=(8, 16, 8), batch=batch, split_k=split)   # col-major C: run transposed
+    _general_case(M, N, K, la=la, lb=lb, ints=True, batch=batch, split_k=split)
+    _general_case(M, N, K, la=la, lb=lb, ab="f16", cd="bf16", bias=True, alpha=-1.25, batch=batch, split_k=split)
+    _general_case(M, N, K, la=la, lb=lb, lc="col", pad=(8, 16, 8), batch=batch, split_k=split)   # col-major C: run transposed
 
 
 def test_unaligned_pointers_and_odd_ld():
