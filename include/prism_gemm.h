@@ -109,12 +109,13 @@ typedef struct prism_gemm_plan {
  * hip_stream   a hipStream_t passed as void*; NULL is the default stream.
  *
  * M == 0 or N == 0: nothing is written, PRISM_OK.  K == 0: C <- bias + beta*C.
- * Any positive sizes, leading dimensions and alignments are accepted.  16-bit
- * operands in either layout run on the fast pipeline when their rows (or
- * columns) start on 16-byte boundaries, K is a multiple of 64 and, for an
- * operand that is not contiguous along K (column-major A, row-major B), M
- * respectively N is a multiple of 8; everything else (fp32 operands included)
- * runs on a staged kernel with the same arithmetic.  For a fixed problem, descriptor and GPU the result is
+ * Any positive sizes, leading dimensions and alignments are accepted.
+ * Operands in either layout run on the fast pipeline when their rows (or
+ * columns) start on 16-byte boundaries, K is a multiple of 128 bytes of
+ * elements (64 of a 16-bit type, 32 of fp32) and, for an operand that is not
+ * contiguous along K (column-major A, row-major B), M respectively N is a
+ * multiple of 16 bytes of elements; everything else runs on a staged kernel
+ * with the same arithmetic.  For a fixed problem, descriptor and GPU the result is
  * bit-for-bit reproducible: split-K partial sums are reduced in slice order.
  */
 PRISM_API prism_status_t prism_gemm(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,

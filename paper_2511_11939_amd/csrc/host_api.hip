@@ -153,14 +153,15 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     // ---- kernel and tile shape
     const int64_t step_k = 128 / ab_esize;  // a K step is 128 bytes of every operand row
     const int64_t ksteps = ceil_div(K, step_k);
-    const bool pitch_ok = p.a_sm < (int64_t{1} << 21) && p.b_sn < (int64_t{1} << 21) && p.b_sk < (int64_t{1} << 21);
-    // B contiguous along n (a row-major B): whole, aligned 16-byte chunks of every k-row
-    const bool b_along_n = p.b_sn == 1 && p.b_sk != 1 && aligned(p.B, 16) && p.b_sk % 8 == 0 && p.N % 8 == 0 &&
-                           (p.batch == 1 || p.batch_b % 8 == 0);
-    const bool a_along_m = p.a_sm == 1 && p.a_sk != 1 && aligned(p.A, 16) && p.a_sk % 8 == 0 && p.M % 8 == 0 &&
-                           (p.batch == 1 || p.batch_a % 8 == 0);
-    const bool pipe_ok = ab_esize == 2 && (p.a_vec || a_along_m) && (p.b_vec || b_along_n) && K % 64 == 0 &&
-                         pitch_ok && p.a_sk < (int64_t{1} << 21);
+    const bool pitch_ok = p.a_sm < (int64_t{1} << 21) && p.b_sn < (int64_t{1} << 21) && p.a_sk < (int64_t{1} << 21) &&
+                          p.b_sk < (int64_t{1} << 21);
+    // An operand contiguous along m (column-major A) or n (row-major B): whole, aligned 16-byte
+    // chunks of every k-row
+    const bool a_along_m = p.a_sm == 1 && p.a_sk != 1 && aligned(p.A, 16) && p.a_sk % epc == 0 && p.M % epc == 0 &&
+                           (p.batch == 1 || p.batch_a % epc == 0);
+    const bool b_along_n = p.b_sn == 1 && p.b_sk != 1 && aligned(p.B, 16) && p.b_sk % epc == 0 && p.N % epc == 0 &&
+                           (p.batch == 1 || p.batch_b % epc == 0);
+    const bool pipe_ok = (p.a_vec || a_along_m) && (p.b_vec || b_along_n) && K % step_k == 0 && pitch_ok;
     int tile_m = prism::kStagedTileM, tile_n = prism::kStagedTileN, waves = prism::kStagedWaves;
     plan.kernel = 1;
     if (pipe_ok) {
@@ -178,6 +179,8 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         }
         // an operand that is not K-contiguous: 128x128 tiles, that operand kept as k-rows in LDS
         if (!p.a_vec || !p.b_vec) cfg = !p.a_vec ? (!p.b_vec ? 4 : 3) : 2;
+        // fp32 operands: 128x128 tiles in all four layout pairs
+        if (ab_esize == 4) cfg = 5 + (p.b_vec ? 0 : 1) + (p.a_vec ? 0 : 2);
         out->pipe_config = cfg;
         tile_m = prism::kPipeConfigs[cfg].tile_m;
         tile_n = prism::kPipeConfigs[cfg].tile_n;
@@ -199,8 +202,10 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
         // 8 or 32).
         const bool small_tiles = plan.kernel != 2 || out->pipe_config != 0;
         const int64_t slots = small_tiles ? 2 * kComputeUnits : kComputeUnits;
-        const int64_t min_slice = plan.kernel != 2 ? kMinSliceStepsStaged : (small_tiles ? 16 : 32);
-        const int64_t min_k = plan.kernel != 2 ? 4 * kMinSliceStepsStaged : 64;
+        // (a K step of fp32 operands holds four times the matrix instructions of a 16-bit one)
+        const bool short_steps = plan.kernel == 2 && ab_esize == 2;
+        const int64_t min_slice = !short_steps ? kMinSliceStepsStaged : (small_tiles ? 16 : 32);
+        const int64_t min_k = !short_steps ? 4 * kMinSliceStepsStaged : 64;
         if (units * 2 <= slots && ksteps >= min_k) {
             want = slots / units;
             if (want > ksteps / min_slice) want = ksteps / min_slice;

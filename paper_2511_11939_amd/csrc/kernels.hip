@@ -19,6 +19,10 @@ const PipeConfig kPipeConfigs[kNumPipeConfigs] = {
     {2, 128, 128, 64, 4, 2, "128x128x64_w4_b_along_n"},
     {3, 128, 128, 64, 4, 2, "128x128x64_w4_a_along_m"},
     {4, 128, 128, 64, 4, 2, "128x128x64_w4_a_along_m_b_along_n"},
+    {5, 128, 128, 32, 4, 2, "f32_128x128x32_w4"},
+    {6, 128, 128, 32, 4, 2, "f32_128x128x32_w4_b_along_n"},
+    {7, 128, 128, 32, 4, 2, "f32_128x128x32_w4_a_along_m"},
+    {8, 128, 128, 32, 4, 2, "f32_128x128x32_w4_a_along_m_b_along_n"},
 };
 
 namespace {
@@ -110,18 +114,19 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Placement q = place<BM, BN>(p, blockIdx.x);
 
-    const char* a_tile = p.A + 2 * (q.batch * p.batch_a + q.m0 * p.a_sm + q.k_begin * p.a_sk);
-    const char* b_tile = p.B + 2 * (q.batch * p.batch_b + q.n0 * p.b_sn + q.k_begin * p.b_sk);
+    constexpr int ES = P::ES;
+    const char* a_tile = p.A + ES * (q.batch * p.batch_a + q.m0 * p.a_sm + q.k_begin * p.a_sk);
+    const char* b_tile = p.B + ES * (q.batch * p.batch_b + q.n0 * p.b_sn + q.k_begin * p.b_sk);
     const int a_rows = p.M - q.m0 < BM ? p.M - q.m0 : BM;
     const int b_rows = p.N - q.n0 < BN ? p.N - q.n0 : BN;
     // pitch of a row of an LDS tile: a row of the matrix (K-contiguous operand) or a k-row
-    const uint32_t a_ld = static_cast<uint32_t>(2 * (p.a_sk == 1 ? p.a_sm : p.a_sk));
-    const uint32_t b_ld = static_cast<uint32_t>(2 * (p.b_sk == 1 ? p.b_sn : p.b_sk));
+    const uint32_t a_ld = static_cast<uint32_t>(ES * (p.a_sk == 1 ? p.a_sm : p.a_sk));
+    const uint32_t b_ld = static_cast<uint32_t>(ES * (p.b_sk == 1 ? p.b_sn : p.b_sk));
 
     typename P::tile_t acc;
     acc.clear();
     P::run(wgp, acc, a_tile, a_ld, a_rows, b_tile, b_ld, b_rows,
-           (q.k_end - q.k_begin) / BK, lds, wave, lane);
+           (q.k_end - q.k_begin) / P::K_PER_STEP, lds, wave, lane);
 
     epilogue<typename P::tile_t, P::MT, P::NT>(wgp, p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
                                                q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane);
@@ -254,6 +259,15 @@ hipError_t launch_pipe_config(int config, const GemmParams& p, int workgroups, h
 
 hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream)
 {
+    if (ab_dtype == DT_F32) {  // fp32 operands: 128x128 tiles, the four layout pairs
+        switch (config) {
+        case 5: return launch_pipe<wg::Pipeline<f32_t, 128, 128, 64, 2, 2, 2>, 128, 128, 64, 2>(p, workgroups, stream);
+        case 6: return launch_pipe<wg::Pipeline<f32_t, 128, 128, 64, 2, 2, 2, true>, 128, 128, 64, 2>(p, workgroups, stream);
+        case 7: return launch_pipe<wg::Pipeline<f32_t, 128, 128, 64, 2, 2, 2, false, true>, 128, 128, 64, 2>(p, workgroups, stream);
+        case 8: return launch_pipe<wg::Pipeline<f32_t, 128, 128, 64, 2, 2, 2, true, true>, 128, 128, 64, 2>(p, workgroups, stream);
+        default: return hipErrorInvalidValue;
+        }
+    }
     return ab_dtype == DT_BF16 ? launch_pipe_config<bf16_t>(config, p, workgroups, stream)
                                : launch_pipe_config<f16_t>(config, p, workgroups, stream);
 }

@@ -13,7 +13,7 @@ struct PipeConfig {
     int tile_m, tile_n, tile_k, waves, stages;
     const char* name;
 };
-constexpr int kNumPipeConfigs = 5;  // 0, 1: both operands K-contiguous; 2-4: B along n, A along m, both
+constexpr int kNumPipeConfigs = 9;  // 0, 1: both operands K-contiguous; 2-4: B along n, A along m, both; 5-8: fp32, same four
 extern const PipeConfig kPipeConfigs[kNumPipeConfigs];
 
 constexpr int kStagedTileM = 128, kStagedTileN = 128, kStagedWaves = 4;

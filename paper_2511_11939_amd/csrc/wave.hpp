@@ -37,6 +37,19 @@ __device__ __forceinline__ f32x4 mfma_block(persp::Wave, f32x4 r, f32x4 c, f32x4
     return acc;
 }
 
+// One matrix instruction of a block: for 16-bit operands the whole block (part 0 of 1), for
+// fp32 the e-th of its four.  Issuing the same e for all blocks before the next e keeps
+// consecutive instructions independent of each other.
+constexpr int mfma_parts(bf16x8) { return 1; }
+constexpr int mfma_parts(f16x8) { return 1; }
+constexpr int mfma_parts(f32x4) { return 4; }
+__device__ __forceinline__ f32x4 mfma_part(persp::Wave w, bf16x8 r, bf16x8 c, int, f32x4 acc) { return mfma_block(w, r, c, acc); }
+__device__ __forceinline__ f32x4 mfma_part(persp::Wave w, f16x8 r, f16x8 c, int, f32x4 acc) { return mfma_block(w, r, c, acc); }
+__device__ __forceinline__ f32x4 mfma_part(persp::Wave, f32x4 r, f32x4 c, int e, f32x4 acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(r[e], c[e], acc, 0, 0, 0);
+}
+
 // Register-blocked wave tile: MT x NT accumulator blocks of 16 x 16.  The B
 // fragment is the MFMA's row operand, so every lane ends up holding runs of
 // four consecutive n for one m, which is what a row-major store wants.

@@ -165,6 +165,8 @@ __device__ __forceinline__ void drain_runs(persp::Wave, const TileT& acc, char* 
 template <typename T, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, bool B_KN = false, bool A_MK = false>
 struct Pipeline {
     using L = lane::TileLayout<BK>;
+    static constexpr int ES = Frag<T>::kElemBytes;
+    static constexpr int K_PER_STEP = L::kRowBytes / ES;  // elements of K one step consumes (BK counts 2-byte units)
     // (With 256x256 tiles the extra fragment addresses of this variant do not fit beside the
     // accumulators: it was built, spilled several hundred registers and ran at half the speed
     // of the 128x128 form, which is the one kept.)
@@ -210,25 +212,29 @@ struct Pipeline {
                                char* lds, int wave, int lane)
     {
         const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
-        constexpr int NM = MT * NT;   // MFMAs per sub-step
-        constexpr int A_READS = A_MK ? 2 : 1, B_READS = B_KN ? 2 : 1;  // LDS reads per fragment
+        constexpr int PARTS = wave::mfma_parts(frag_t{});  // matrix instructions per block and sub-step
+        constexpr int NM = MT * NT * PARTS;                // MFMAs per sub-step
+        constexpr int A_READS = A_MK && ES == 2 ? 2 : 1, B_READS = B_KN && ES == 2 ? 2 : 1;  // LDS reads per fragment
         constexpr int NR = A_READS * MT + B_READS * NT;                // fragment reads per sub-step
         // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave) of COPY_ROWS rows;
         //    a lane fills one chunk position of one row with the logical chunk the swizzle wants.
         const int sub_row = lane / L::kChunksPerRow;
         const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
         uint32_t g_off[COPIES];
-        // An operand kept as k-rows: a k-row of the tile is 256 bytes (128 elements) and a
-        // wave-wide copy moves four of them.  The 16-byte chunk c of k-row k sits at position
+        // An operand kept as k-rows: a k-row of the tile is 128 elements and a wave-wide copy
+        // moves 1024 bytes of them.  16-bit types: the 16-byte chunk c of k-row k sits at position
         // c ^ 2*(k%4), so that the four k-rows a transposing read touches fall on four different
-        // 32-byte bank groups.  `cols` counts the elements of a k-row that exist (a multiple of
-        // 8); chunks beyond them re-read the last one that exists and only feed results that
-        // are never stored.
-        constexpr int KN_ROW_BYTES = 256, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
+        // 32-byte bank groups.  fp32: at position c ^ 4*((k/4)%2), so that the four k-rows of a
+        // 4-byte gather (k = 4g + e for lane group g) alternate between the two halves of the
+        // banks.  `cols` counts the elements of a k-row that exist (whole chunks); chunks beyond
+        // them re-read the last one that exists and only feed results that are never stored.
+        constexpr int KN_ROW_BYTES = 128 * ES, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
+        constexpr int PER_CHUNK = lane::kChunkBytes / ES;
         auto k_row_offset = [&](int i, uint32_t ld, int cols) __attribute__((always_inline)) {
             const int k_row = (i * NW + wave) * KN_ROWS + lane / KN_CHUNKS;
-            int c = (lane % KN_CHUNKS) ^ ((k_row & 3) << 1);
-            const int last = (cols - 1) / 8;
+            const int swz = ES == 2 ? (k_row & 3) << 1 : ((k_row >> 2) & 1) << 2;
+            int c = (lane % KN_CHUNKS) ^ swz;
+            const int last = (cols - 1) / PER_CHUNK;
             c = c < last ? c : last;
             return static_cast<uint32_t>(k_row) * ld + c * lane::kChunkBytes;
         };
@@ -257,8 +263,8 @@ struct Pipeline {
         // copy number c (0 .. COPIES-1) of K step `step` into slot `stage`
         auto copy = [&](int c, int step, int stage) __attribute__((always_inline)) {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
-            const int64_t a_bytes = A_MK ? static_cast<int64_t>(step) * BK * a_ld : k_bytes;
-            const int64_t b_bytes = B_KN ? static_cast<int64_t>(step) * BK * b_ld : k_bytes;
+            const int64_t a_bytes = A_MK ? static_cast<int64_t>(step) * K_PER_STEP * a_ld : k_bytes;
+            const int64_t b_bytes = B_KN ? static_cast<int64_t>(step) * K_PER_STEP * b_ld : k_bytes;
             const uint32_t slot = lds0 + stage * STAGE_BYTES;
             if (c < A_COPIES) copy_async_16(wv, a_tile + a_bytes, g_off[c], slot, c * NW * 1024);
             else copy_async_16(wv, b_tile + b_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
@@ -276,6 +282,17 @@ struct Pipeline {
             return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)src);
         };
 
+        // fp32 fragment from k-rows: element e of lane (x, g) is the value at k-row 16*ksub + 4g + e,
+        // element first + x; nothing to transpose, four 4-byte reads.
+        auto gather_k_rows = [&](const char* tile, int first, int ksub) __attribute__((always_inline)) {
+            const int n = first + (lane & 15), g = lane >> 4;
+            const char* src = tile + (16 * ksub + 4 * g) * KN_ROW_BYTES + (((n >> 2) ^ ((g & 1) << 2)) * lane::kChunkBytes) + (n & 3) * 4;
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = *reinterpret_cast<const float*>(src + e * KN_ROW_BYTES);
+            return v;
+        };
+
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
         using v4s = __attribute__((ext_vector_type(4))) short;
@@ -285,12 +302,14 @@ struct Pipeline {
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
         auto read_a = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {  // x: fragment * A_READS + half
             const char* st = lds + stage * STAGE_BYTES;
-            if constexpr (A_MK) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            if constexpr (A_MK && ES == 2) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            else if constexpr (A_MK) fa[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, a_row0 + lane::kBlock * x, ksub));
             else fa[buf][x] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * x, ksub, lane);
         };
         auto read_b = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES + A_BYTES;
-            if constexpr (B_KN) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            if constexpr (B_KN && ES == 2) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            else if constexpr (B_KN) fb[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, b_row0 + lane::kBlock * x, ksub));
             else fb[buf][x] = lane::load_fragment<T, BK>(wv.lane(), st, b_row0 + lane::kBlock * x, ksub, lane);
         };
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
@@ -299,16 +318,17 @@ struct Pipeline {
             else read_a(r - B_READS * NT, buf, stage, ksub);
         };
         auto whole = [](v4s lo, v4s hi) __attribute__((always_inline)) {
-            return __builtin_bit_cast(frag_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            if constexpr (ES == 2) return __builtin_bit_cast(frag_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            else return frag_t{};
         };
         auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
-            const int i = m / NT, j = m % NT;
+            const int e = m / (MT * NT), blk = m % (MT * NT), i = blk / NT, j = blk % NT;
             frag_t a, b;
-            if constexpr (A_MK) a = whole(fah[buf][i][0], fah[buf][i][1]);
+            if constexpr (A_MK && ES == 2) a = whole(fah[buf][i][0], fah[buf][i][1]);
             else a = fa[buf][i];
-            if constexpr (B_KN) b = whole(fbh[buf][j][0], fbh[buf][j][1]);
+            if constexpr (B_KN && ES == 2) b = whole(fbh[buf][j][0], fbh[buf][j][1]);
             else b = fb[buf][j];
-            acc.acc[i][j] = wave::mfma_block(wv, b, a, acc.acc[i][j]);
+            acc.acc[i][j] = wave::mfma_part(wv, b, a, e, acc.acc[i][j]);
         };
 
         // -- prologue: fill the slots, wait for step 0, fetch its first fragments

@@ -196,7 +196,9 @@ def test_fp32_operands_need_an_fp32_result():
         assert P.prism_gemm(d, 64, 64, 64, FAKE_A, 64, FAKE_B, 64, FAKE_C, 64, None) == S.UNSUPPORTED
     d = P.make_desc(ab_dtype="f32", c_dtype="f32", layout_b="row")
     s, plan = P.prism_gemm_plan(d, 4096, 4096, 4096, None, 4096, 0, None, 4096, 0, None, 4096, 0, 1)
-    assert s == S.OK and plan.kernel == 1 and plan.tile_k == 32 and plan.workgroups == 32 * 32
+    assert s == S.OK and plan.kernel == 2 and plan.tile_m == 128 and plan.tile_k == 32 and plan.workgroups == 32 * 32
+    s, plan = P.prism_gemm_plan(d, 4096, 4096, 4100, None, 4100, 0, None, 4096, 0, None, 4096, 0, 1)
+    assert s == S.OK and plan.kernel == 1                       # K not a multiple of 32: staged kernel
     # overlap is measured in bytes of the real element size
     assert P.prism_gemm(d, 64, 64, 64, FAKE_A, 64, FAKE_B, 64, FAKE_A + 64 * 64 * 4 - 4, 64, None) == S.INVALID_ARG
     s, _ = P.prism_gemm_plan(d, 64, 64, 64, FAKE_A, 64, 0, FAKE_B, 64, 0, FAKE_A + 64 * 64 * 4, 64, 0, 1)

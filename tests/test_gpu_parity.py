@@ -315,7 +315,7 @@ def test_sgemm_4096_workload_sampled_rows():
     w = CONFIGS["sgemm_4096_rowrow"]
     inp = make_inputs(w)
     c, plan = run_workload(w, inp)
-    assert plan["kernel"] == 1 and plan["tile_k"] == 32
+    assert plan["kernel"] == 2 and plan["tile_m"] == 128 and plan["tile_k"] == 32
     rows = tile_probe_rows(w.M, plan["tile_m"], per_tile=(0, 15, 16, 63, 64, 127))
     assert_matches_oracle(w, inp, c, rows=rows)
     c2, _ = run_workload(w, inp)
