@@ -77,6 +77,23 @@ load_fragment(persp::Lane, const char* tile, int row0, int ksub, int lane)
     return __builtin_bit_cast(typename Frag<T>::type, raw);
 }
 
+// The same fragment with the address split into what depends on the lane only and what does
+// not: for a block of 16 rows that starts at a multiple of 8 rows the swizzle of a lane's row
+// is that of (lane % 16), so  offset(row0 + lane%16, chunk) = row0 * row bytes + lane part.
+// Callers keep the lane part (one value per ksub) in a register and add uniform and constant
+// terms, which then fold into the instruction's offset field.
+template <int BK>
+__device__ __forceinline__ uint32_t fragment_lane_part(persp::Lane, int ksub, int lane)
+{
+    return TileLayout<BK>::offset(lane & 15, 4 * ksub + (lane >> 4));
+}
+template <typename T>
+__device__ __forceinline__ typename Frag<T>::type load_fragment_at(persp::Lane, const char* block_rows, uint32_t lane_part)
+{
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(block_rows + lane_part);
+    return __builtin_bit_cast(typename Frag<T>::type, raw);
+}
+
 // ---- accumulator layout of the 16x16 MFMA -----------------------------------------
 // With the fragment of the "row" operand r and the "column" operand c,
 // D = r * c^T is spread so that lane l holds column l%16 and, in register i

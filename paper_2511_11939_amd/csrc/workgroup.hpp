@@ -296,6 +296,10 @@ struct Pipeline {
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
         using v4s = __attribute__((ext_vector_type(4))) short;
+        static_assert(WTM % 8 == 0 && WTN % 8 == 0 && lane::kBlock % 8 == 0, "row blocks start at multiples of 8 rows");
+        uint32_t frag_part[KSUB];  // the lane's share of a fragment address, one per sub-step
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) frag_part[ks] = lane::fragment_lane_part<BK>(wv.lane(), ks, lane);
         frag_t fa[2][MT], fb[2][NT];
         v4s fah[2][MT][2], fbh[2][NT][2];  // operands kept as k-rows: the two halves of every fragment
         // read number r (0 .. NR-1) of sub-step ksub of slot `stage` into buffer `buf`;
@@ -304,13 +308,13 @@ struct Pipeline {
             const char* st = lds + stage * STAGE_BYTES;
             if constexpr (A_MK && ES == 2) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0 + lane::kBlock * (x / 2), ksub, x % 2);
             else if constexpr (A_MK) fa[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, a_row0 + lane::kBlock * x, ksub));
-            else fa[buf][x] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * x, ksub, lane);
+            else fa[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + (a_row0 + lane::kBlock * x) * L::kRowBytes, frag_part[ksub]);
         };
         auto read_b = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES + A_BYTES;
             if constexpr (B_KN && ES == 2) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0 + lane::kBlock * (x / 2), ksub, x % 2);
             else if constexpr (B_KN) fb[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, b_row0 + lane::kBlock * x, ksub));
-            else fb[buf][x] = lane::load_fragment<T, BK>(wv.lane(), st, b_row0 + lane::kBlock * x, ksub, lane);
+            else fb[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + (b_row0 + lane::kBlock * x) * L::kRowBytes, frag_part[ksub]);
         };
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             if (r < A_READS) read_a(r, buf, stage, ksub);
@@ -548,11 +552,14 @@ struct PersistentPipe {
             if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], slot, c * NW * 1024);
             else copy_async_16(wv, b_src, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
         };
+        uint32_t frag_part[KSUB];  // the lane's share of a fragment address, one per sub-step
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) frag_part[ks] = lane::fragment_lane_part<BK>(wv.lane(), ks, lane);
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES;
-            if (r == 0) fa[buf][0] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0, ksub, lane);
-            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment<T, BK>(wv.lane(), st + A_BYTES, b_row0 + lane::kBlock * (r - 1), ksub, lane);
-            else fa[buf][r - NT] = lane::load_fragment<T, BK>(wv.lane(), st, a_row0 + lane::kBlock * (r - NT), ksub, lane);
+            if (r == 0) fa[buf][0] = lane::load_fragment_at<T>(wv.lane(), st + a_row0 * L::kRowBytes, frag_part[ksub]);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment_at<T>(wv.lane(), st + A_BYTES + (b_row0 + lane::kBlock * (r - 1)) * L::kRowBytes, frag_part[ksub]);
+            else fa[buf][r - NT] = lane::load_fragment_at<T>(wv.lane(), st + (a_row0 + lane::kBlock * (r - NT)) * L::kRowBytes, frag_part[ksub]);
         };
         auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
             const int i = m / NT, j = m % NT;
