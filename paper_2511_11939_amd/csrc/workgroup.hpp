@@ -167,11 +167,11 @@ struct Pipeline {
     using L = lane::TileLayout<BK>;
     static constexpr int ES = Frag<T>::kElemBytes;
     static constexpr int K_PER_STEP = L::kRowBytes / ES;  // elements of K one step consumes (BK counts 2-byte units)
-    // (With 256x256 tiles the extra fragment addresses of this variant do not fit beside the
-    // accumulators: it was built, spilled several hundred registers and ran at half the speed
-    // of the 128x128 form, which is the one kept.)
-    static_assert(!B_KN || (BK == 64 && BN == 128), "n-contiguous B: 64 k-rows of 128 elements");
-    static_assert(!A_MK || (BK == 64 && BM == 128), "m-contiguous A: 64 k-rows of 128 elements");
+    // (A 256x256 form of the k-row variants was built twice; beside 256 accumulators it spills
+    // several hundred registers and runs at half the speed of the 128x128 form.)
+    static_assert(!B_KN || (BK == 64 && BN == 128), "n-contiguous B: k-rows of 128 elements");
+    static_assert(!A_MK || (BK == 64 && BM == 128), "m-contiguous A: k-rows of 128 elements");
+    static_assert(!(A_MK && B_KN) || BM == BN, "both operands as k-rows: square tile");
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -228,7 +228,8 @@ struct Pipeline {
         // 4-byte gather (k = 4g + e for lane group g) alternate between the two halves of the
         // banks.  `cols` counts the elements of a k-row that exist (whole chunks); chunks beyond
         // them re-read the last one that exists and only feed results that are never stored.
-        constexpr int KN_ROW_BYTES = 128 * ES, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
+        constexpr int KN_WIDTH = B_KN ? BN : BM;  // elements of a k-row (with both operands as k-rows BM == BN)
+        constexpr int KN_ROW_BYTES = KN_WIDTH * ES, KN_CHUNKS = KN_ROW_BYTES / lane::kChunkBytes, KN_ROWS = 1024 / KN_ROW_BYTES;
         constexpr int PER_CHUNK = lane::kChunkBytes / ES;
         auto k_row_offset = [&](int i, uint32_t ld, int cols) __attribute__((always_inline)) {
             const int k_row = (i * NW + wave) * KN_ROWS + lane / KN_CHUNKS;
@@ -269,19 +270,25 @@ struct Pipeline {
             if (c < A_COPIES) copy_async_16(wv, a_tile + a_bytes, g_off[c], slot, c * NW * 1024);
             else copy_async_16(wv, b_tile + b_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
         };
-        // Half h (4 consecutive k) of the fragment whose 16 rows start at element `first` of
-        // the k-rows of the tile at `tile`.  The 16 lanes of a group point at 4 k-rows x 16
-        // elements (lane i: k-row i/4, quad i%4); the transposing read hands lane i the four k
-        // of element first + i.
-        auto read_k_rows = [&](const char* tile, int first, int ksub, int h) __attribute__((always_inline)) {
+        // Half h (4 consecutive k) of the fragment whose 16 rows start at element `first` (a
+        // multiple of 16, the wave's first one a multiple of 64) of the k-rows of the tile at
+        // `tile`.  The 16 lanes of a group point at 4 k-rows x 16 elements (lane i: k-row i/4,
+        // quad i%4); the transposing read hands lane i the four k of element first + i.  The
+        // address is a constant (block of 64 elements, sub-step, half) plus a per-lane part
+        // that depends only on which 16 of the 64 elements are read (the swizzle stays inside
+        // a group of 8 chunks), so four registers serve all reads.
+        uint32_t k_rows_part[4];
+        {
+            const int i = lane & 15, kq = lane >> 4, s_row = i >> 2, x = (i & 3) >> 1;
+#pragma unroll
+            for (int jl = 0; jl < 4; ++jl)
+                k_rows_part[jl] = (8 * kq + s_row) * KN_ROW_BYTES + (((2 * jl + x) ^ (s_row << 1)) * lane::kChunkBytes) + (i & 1) * 8;
+        }
+        auto read_k_rows = [&](const char* tile, int row0, int j, int ksub, int h) __attribute__((always_inline)) {
             using v4s = __attribute__((ext_vector_type(4))) short;
-            const int i = lane & 15, kq = lane >> 4;
-            const int n = first + 4 * (i & 3);
-            const int k_row = 32 * ksub + 8 * kq + 4 * h + (i >> 2);
-            const char* src = tile + k_row * KN_ROW_BYTES + (((n >> 3) ^ ((i >> 2) << 1)) * lane::kChunkBytes) + (n & 7) * 2;
+            const char* src = tile + ((row0 >> 3) + 8 * (j / 4)) * lane::kChunkBytes + (32 * ksub + 4 * h) * KN_ROW_BYTES + k_rows_part[j % 4];
             return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)src);
         };
-
         // fp32 fragment from k-rows: element e of lane (x, g) is the value at k-row 16*ksub + 4g + e,
         // element first + x; nothing to transpose, four 4-byte reads.
         auto gather_k_rows = [&](const char* tile, int first, int ksub) __attribute__((always_inline)) {
@@ -306,13 +313,13 @@ struct Pipeline {
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
         auto read_a = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {  // x: fragment * A_READS + half
             const char* st = lds + stage * STAGE_BYTES;
-            if constexpr (A_MK && ES == 2) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            if constexpr (A_MK && ES == 2) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0, x / 2, ksub, x % 2);
             else if constexpr (A_MK) fa[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, a_row0 + lane::kBlock * x, ksub));
             else fa[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + (a_row0 + lane::kBlock * x) * L::kRowBytes, frag_part[ksub]);
         };
         auto read_b = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {
             const char* st = lds + stage * STAGE_BYTES + A_BYTES;
-            if constexpr (B_KN && ES == 2) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0 + lane::kBlock * (x / 2), ksub, x % 2);
+            if constexpr (B_KN && ES == 2) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0, x / 2, ksub, x % 2);
             else if constexpr (B_KN) fb[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, b_row0 + lane::kBlock * x, ksub));
             else fb[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + (b_row0 + lane::kBlock * x) * L::kRowBytes, frag_part[ksub]);
         };
