@@ -83,7 +83,7 @@ typedef struct prism_gemm_desc {
  */
 typedef struct prism_gemm_plan {
     int32_t kernel;          /* 0 = nothing to launch, 1 = staged (any layout/alignment),
-                                2 = direct-to-LDS pipeline (K-contiguous, aligned),
+                                2 = direct-to-LDS pipeline (aligned operands),
                                 3 = the same pipeline, persistent: used for more tiles
                                     than compute units with short K loops              */
     int32_t tile_m, tile_n, tile_k; /* workgroup tile                                */
