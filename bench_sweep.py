@@ -19,8 +19,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def timed(fn, stream, reps, warmup=3):
+def timed(fn, stream, reps, warmup=3, ramp_seconds=0.15):
+    """Microseconds per call from stream events, after enough untimed calls for the clock
+    governor to reach its sustained state (the same for both libraries)."""
+    import time
     import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < ramp_seconds:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
