@@ -20,3 +20,29 @@ def test_traffic_figures_are_tied_to_the_kernel_sources():
     assert len(digest) == 16
     for name, (nbytes, tag) in bench.MEASURED_TRAFFIC.items():
         assert nbytes > 0 and len(tag) == 16, name
+
+
+import json
+
+import pytest
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("workload", ["cfg2_4096_bf16", "cfg5_batched_512", "scan_u32_2p28"])
+def test_bench_prints_one_json_line_with_the_contract_keys(workload):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", workload, "--steps", "3",
+                        "--warmup", "1", "--ramp-seconds", "0.05", "--cpu-rows", "64"],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["vs_baseline"] is None
+    assert d["config"]["workload"] == workload and "model" not in d["config"]
+    roof = d["roofline"]
+    assert roof["bound"] in ("mfma", "hbm") and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["cores"] >= 1
+    assert d["parity_on_sample"]["ok"] is True
