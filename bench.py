@@ -1,8 +1,11 @@
 #!/usr/bin/env python3
-"""Throughput of the GEMM hot path on one MI355X.
+"""Throughput of the GEMM hot path (and of the sgemm and scan workloads) on one MI355X.
 
-A step is one call of prism_gemm(_batched) on the named synthetic workload with
-the operands already resident in HBM.  Prints one JSON line.
+A step is one call of prism_gemm(_batched) (or prism_scan_u32) on the named synthetic
+workload with the operands already resident in HBM.  Order of a run: untimed launches of
+the same step for --ramp-seconds (the GPU's clock governor needs about 0.1 s of load to
+reach the clock it sustains; reported as "clock_ramp"), then --warmup untimed steps, then
+exactly --steps timed steps between two events on the launch stream.  Prints one JSON line.
 """
 from __future__ import annotations
 
