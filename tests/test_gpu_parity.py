@@ -434,3 +434,14 @@ def _sweep_cases(count, seed):
 def test_seeded_sweep(case):
     c = dict(case)
     _general_case(c.pop("M"), c.pop("N"), c.pop("K"), **c)
+
+
+@pytest.mark.parametrize("M,N,K,kw", [
+    (1, 8, 100_000, dict()),                                   # one row, very long K (staged kernel, automatic split)
+    (8192, 16, 64, dict()),                                    # tall and skinny
+    (16, 8192, 128, dict(lb="row")),                           # wide, row-major B
+    (2, 3, 65_536, dict(ab="f32", lb="row")),                  # fp32, long K
+    (4096, 8, 4096, dict(cd="bf16", bias=True)),               # a matrix-vector-like product with bias
+])
+def test_extreme_aspect_ratios(M, N, K, kw):
+    _general_case(M, N, K, ints=True, **kw)
