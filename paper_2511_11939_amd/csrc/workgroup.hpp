@@ -499,7 +499,7 @@ __device__ __forceinline__ void drain_runs16(persp::Wave, const TileT& acc, char
 // which together are exactly the 160 KiB of a compute unit; the patches are separate so
 // that the epilogue of a tile can run while the slots already hold the next tile.
 // ------------------------------------------------------------------------------------
-template <typename T, int HEADN = 4>
+template <typename T, int HEADN = 0>  // copies of a step left for the start of the next one (0: measured best)
 struct PersistentPipe {
     using L = lane::TileLayout<64>;
     static constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2, NW = 4, THREADS = 256;
