@@ -258,7 +258,7 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
                     "device_copy_gbs": round(copy_ceiling_gbs(), 1)}
-    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent"}.get(plan.kernel, "none")
+    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent", 4: "gemm_streamk"}.get(plan.kernel, "none")
     roofline["launch_us"] = round(launch_ms * 1e3, 2)
     measured = MEASURED_TRAFFIC.get(w.name)
     if measured and measured[1] == source_digest():

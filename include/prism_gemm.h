@@ -85,7 +85,9 @@ typedef struct prism_gemm_plan {
     int32_t kernel;          /* 0 = nothing to launch, 1 = staged (any layout/alignment),
                                 2 = direct-to-LDS pipeline (aligned operands),
                                 3 = the same pipeline, persistent: used for more tiles
-                                    than compute units with short K loops              */
+                                    than compute units with short K loops,
+                                4 = its stream-K form (only with PRISM_STREAMK=1 in the
+                                    environment; needs workspace_bytes of workspace)   */
     int32_t tile_m, tile_n, tile_k; /* workgroup tile                                */
     int32_t waves;           /* wavefronts per workgroup                              */
     int32_t split_k;         /* K slices actually used (>= 1)                         */

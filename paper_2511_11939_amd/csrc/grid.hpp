@@ -43,6 +43,30 @@ struct TileCoord {
     int tile_m, tile_n, unit;
 };
 
+// Position r in the locality order -> tile: groups of kGroupRows tile rows, m fastest, so that
+// a contiguous run of positions is a compact block sharing few A and B panels.
+__host__ __device__ inline void tile_at(int r, int tiles_m, int tiles_n, int& tile_m, int& tile_n)
+{
+    const int group_span = kGroupRows * tiles_n;
+    const int group = r / group_span;
+    const int first_m = group * kGroupRows;
+    const int rows = tiles_m - first_m < kGroupRows ? tiles_m - first_m : kGroupRows;
+    const int in_group = r % group_span;
+    tile_m = first_m + in_group % rows;
+    tile_n = in_group / rows;
+}
+
+// The share of die `die` when `total` positions are dealt to the dies as contiguous runs
+// (the first `total % kDies` dies take one more): first position and count.
+__host__ __device__ inline void die_run(int die, int total, int& first, int& count)
+{
+    const int per = (total + kDies - 1) / kDies;
+    int tall = total % kDies;
+    if (tall == 0) tall = kDies;
+    first = die < tall ? die * per : tall * per + (die - tall) * (per - 1);
+    count = die < tall ? per : per - 1;
+}
+
 // Workgroup id -> (tile, unit).  Step 1 undoes the round-robin dealing so that
 // the workgroups resident on one die form a contiguous run of a tile order;
 // step 2 walks the tiles in groups of kGroupRows tile rows, m fastest, so that
@@ -50,23 +74,12 @@ struct TileCoord {
 __host__ __device__ inline TileCoord schedule(int wg, int tiles_m, int tiles_n, int units)
 {
     const int tiles = tiles_m * tiles_n;
-    const int total = tiles * units;
-    const int per = (total + kDies - 1) / kDies;
-    int tall = total % kDies;
-    if (tall == 0) tall = kDies;
-    const int die = wg % kDies, local = wg / kDies;
-    const int q = die < tall ? die * per + local
-                             : tall * per + (die - tall) * (per - 1) + local;
+    int first, count;
+    die_run(wg % kDies, tiles * units, first, count);
+    const int q = first + wg / kDies;
     TileCoord t;
     t.unit = q / tiles;
-    const int r = q % tiles;
-    const int group_span = kGroupRows * tiles_n;
-    const int group = r / group_span;
-    const int first_m = group * kGroupRows;
-    const int rows = tiles_m - first_m < kGroupRows ? tiles_m - first_m : kGroupRows;
-    const int in_group = r % group_span;
-    t.tile_m = first_m + in_group % rows;
-    t.tile_n = in_group / rows;
+    tile_at(q % tiles, tiles_m, tiles_n, t.tile_m, t.tile_n);
     return t;
 }
 

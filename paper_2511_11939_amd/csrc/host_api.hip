@@ -252,6 +252,31 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
             if (plan.workgroups > kComputeUnits) plan.workgroups = kComputeUnits;
         }
     }
+    // Stream-K (opt-in, PRISM_STREAMK=1): the K steps of all 256x256 tiles are dealt evenly to 256
+    // workgroups, which exchange partial tiles through the workspace.  It evens out a badly
+    // filled last round of compute units (5120^3: 400 tiles, a round of 256 and one of 144), but
+    // the workgroups of a die then no longer walk K in step and stop sharing operand panels in
+    // the L2: measured 269 against 190 us on 5120^3 and 416 against 343 us on 6144^3, so the
+    // library never chooses it by itself.  One problem, no K split, an even number of K steps;
+    // without the workspace it falls back to one workgroup per tile.
+    {
+        const char* e = std::getenv("PRISM_STREAMK");
+        const bool wanted = e && e[0] == '1';
+        const bool possible = (plan.kernel == 2 || plan.kernel == 3) && out->pipe_config == 0 && batch == 1 && split == 1 &&
+                              d->split_k == 0 && ksteps % 2 == 0 && ksteps >= 2 && units >= kComputeUnits;
+        const bool have_ws = !need_pointers || (d->workspace && d->workspace_bytes >= prism::kStreamKWorkspaceBytes &&
+                                                aligned(d->workspace, 16));
+        if (possible && wanted) {
+            ws_need = prism::kStreamKWorkspaceBytes;
+            if (have_ws) {
+                plan.kernel = 4;
+                plan.workgroups = prism::kStreamKWorkgroups;
+                p.partial = static_cast<float*>(d->workspace);
+            } else {
+                ws_need = 0;
+            }
+        }
+    }
     plan.workspace_bytes = ws_need;
     if (plan.workgroups > kIntMax) return PRISM_ERR_INVALID_ARG;
     return PRISM_OK;
@@ -262,7 +287,9 @@ prism_status_t run(const Problem& pr, hipStream_t stream)
     const GemmParams& p = pr.p;
     if (p.M == 0 || p.N == 0 || p.batch == 0) return PRISM_OK;
     hipError_t e = hipSuccess;
-    if (pr.plan.kernel == 3)
+    if (pr.plan.kernel == 4)
+        e = prism::launch_streamk(pr.ab_dtype, p, stream);
+    else if (pr.plan.kernel == 3)
         e = prism::launch_persistent(pr.ab_dtype, p, pr.total_units, static_cast<int>(pr.plan.workgroups), stream);
     else if (pr.plan.kernel == 2)
         e = prism::launch_pipelined(pr.pipe_config, pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);

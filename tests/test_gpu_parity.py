@@ -346,6 +346,38 @@ def test_operands_not_contiguous_along_k_on_the_pipeline(la, lb, M, N, K, batch,
     _general_case(M, N, K, la=la, lb=lb, lc="col", pad=(8, 16, 8), batch=batch, split_k=split)   # col-major C: run transposed
 
 
+@pytest.mark.parametrize("M,N,K", [(4352, 4352, 512), (4300, 4200, 256), (4096, 4608, 1152), (8192, 2304, 128)])
+def test_stream_k(M, N, K, monkeypatch):
+    """The K steps of all tiles dealt evenly to 256 workgroups that hand partial tiles over
+    through the workspace: every entry against the oracle, exact on integers, the same bits in
+    every run."""
+    monkeypatch.setenv("PRISM_STREAMK", "1")
+    desc = P.make_desc(c_dtype="f32")
+    s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, 0, None, K, 0, None, N, 0, 1)
+    assert s == 0 and plan.kernel == 4 and plan.workgroups == 256 and plan.workspace_bytes == 4096 + 256 * 256 * 256 * 4
+    _general_case(M, N, K, ints=True)
+    _general_case(M, N, K, ab="f16", cd="bf16", bias=True, alpha=-1.25, seed=5)
+    # run to run bit-identical, and identical to one workgroup per tile on integers
+    rng = np.random.default_rng(3)
+    a = to_dev(to_bf16_bits(rng.standard_normal(M * K).astype(np.float32)))
+    b = to_dev(to_bf16_bits(rng.standard_normal(N * K).astype(np.float32)))
+    outs = []
+    for _ in range(2):
+        c = alloc_c(M * N, "f32")
+        d = P.make_desc(c_dtype="f32")
+        ws = workspace_for(d, M, N, K)
+        assert ws is not None
+        P.gemm(a, b, c, M=M, N=N, K=K, desc=d)
+        torch.cuda.synchronize()
+        outs.append(c.cpu().numpy())
+    assert (outs[0] == outs[1]).all()
+    # without the workspace the call falls back to one workgroup per tile and still succeeds
+    c = alloc_c(M * N, "f32")
+    P.gemm(a, b, c, M=M, N=N, K=K, desc=P.make_desc(c_dtype="f32"))
+    torch.cuda.synchronize()
+    assert np.abs(c.cpu().numpy() - outs[0]).max() <= 1e-3 * np.abs(outs[0]).max()
+
+
 def test_unaligned_pointers_and_odd_ld():
     _general_case(96, 80, 128, pad=(1, 1, 1), offset=1, bias=True)
     _general_case(96, 80, 128, pad=(0, 0, 0), offset=3, cd="bf16")
