@@ -149,12 +149,12 @@ __device__ __forceinline__ void finish4_any(const GemmParams& p, char* c_problem
 // scale, add the (pre-loaded) bias, convert, store as one or two 16-byte pieces.
 // With alpha == 1 and a zero bias the arithmetic is exact, so there is no
 // separate path for a plain product.
-template <int OUT>
+template <int OUT, bool BIAS>
 __device__ __forceinline__ void finish_run(char* dst, float alpha, const float (&bias)[8], f32x4 lo, f32x4 hi)
 {
     float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
-    for (int q = 0; q < 8; ++q) o[q] = alpha * o[q] + bias[q];
+    for (int q = 0; q < 8; ++q) o[q] = BIAS ? alpha * o[q] + bias[q] : alpha * o[q];
     if constexpr (OUT == DT_F32) {
         reinterpret_cast<f32x4*>(dst)[0] = f32x4{o[0], o[1], o[2], o[3]};
         reinterpret_cast<f32x4*>(dst)[1] = f32x4{o[4], o[5], o[6], o[7]};
@@ -168,6 +168,24 @@ __device__ __forceinline__ void finish_run(char* dst, float alpha, const float (
         }
         *reinterpret_cast<u32x4*>(dst) = u32x4{w[0], w[1], w[2], w[3]};
     }
+}
+
+// The same eight results as the 16 bytes of a 16-bit output type, not yet stored.
+template <int OUT, bool BIAS>
+__device__ __forceinline__ u32x4 pack_run(float alpha, const float (&bias)[8], f32x4 lo, f32x4 hi)
+{
+    static_assert(OUT == DT_BF16 || OUT == DT_F16, "16-bit output types");
+    float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    uint32_t w[4];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) o[q] = BIAS ? alpha * o[q] + bias[q] : alpha * o[q];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t a = OUT == DT_BF16 ? lane::to_bf16_bits(o[2 * q]) : lane::to_f16_bits(o[2 * q]);
+        const uint32_t b = OUT == DT_BF16 ? lane::to_bf16_bits(o[2 * q + 1]) : lane::to_f16_bits(o[2 * q + 1]);
+        w[q] = a | (b << 16);
+    }
+    return u32x4{w[0], w[1], w[2], w[3]};
 }
 
 // Raw fp32 partial sums of one K slice.

@@ -57,82 +57,150 @@ struct Addends {
     int count = 0;
 };
 
-template <typename TileT, int MT, int NT, bool OWN_PATCH = false>
+template <typename TileT, int MT, int NT, bool OWN_PATCH = false, bool PAIRED = false, bool ADD = false>
 __device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams& p, const Placement& q, const TileT& acc,
                                          int m_wave, int n_wave, char* lds, int wave, int lane, Addends add = Addends{})
 {
     const persp::Wave wv = wgp.wave();
+    const int esize = p.c_dtype == DT_F32 ? 4 : 2;
+    char* c_problem = p.C + static_cast<int64_t>(q.batch) * p.batch_c * esize;
+    const bool inside = m_wave + lane::kBlock * MT <= p.M && n_wave + lane::kBlock * NT <= p.N;
+    const bool fast = p.split_k == 1 && inside && p.c_vec8 && p.beta == 0.0f && !(p.bias && p.bias_along_m);
+    auto out_type = [&](auto&& run) {
+        if (p.c_dtype == DT_BF16) run(std::integral_constant<int, DT_BF16>{});
+        else if (p.c_dtype == DT_F16) run(std::integral_constant<int, DT_F16>{});
+        else run(std::integral_constant<int, DT_F32>{});
+    };
     char* patch = lds;
     if constexpr (!OWN_PATCH) {
-        wg::sync(wgp);
+        wg::sync(wgp);  // every wave has finished with the operand slots: they become patches
         patch = lds + wave * wg::drain_patch_bytes(NT);
     }
+    if constexpr (PAIRED) {
+        if (fast) {
+            // Common case: whole wave tile inside C, aligned rows, nothing to read back.  Every
+            // lane holds runs of eight consecutive n of row lane % 16 of each block row and
+            // finishes them itself.  A 16-bit result then passes through the patch once, to leave
+            // as whole rows (full cache lines per store instruction, written past the caches'
+            // retention: C is not read again by this kernel); an fp32 result goes straight out.
+            constexpr int RUNS = NT / 2;
+            const int n_lane = n_wave + 8 * (lane >> 4);
+            const int64_t row_bytes = p.ldc * esize;
+            const float* add_lane = add.first + (m_wave - q.m0 + (lane & 15)) * kPartialSide + (n_lane - q.n0);
+            auto run = [&](auto out_c, auto bias_c) {
+                constexpr int OUT = decltype(out_c)::value;
+                constexpr bool BIAS = decltype(bias_c)::value;
+                float bias[BIAS ? RUNS : 1][8];
+                if constexpr (BIAS) {
+#pragma unroll
+                    for (int s = 0; s < RUNS; ++s) {
+                        const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + n_lane + 32 * s);
+                        const f32x4 b1 = *reinterpret_cast<const f32x4*>(p.bias + n_lane + 32 * s + 4);
+                        bias[s][0] = b0[0]; bias[s][1] = b0[1]; bias[s][2] = b0[2]; bias[s][3] = b0[3];
+                        bias[s][4] = b1[0]; bias[s][5] = b1[1]; bias[s][6] = b1[2]; bias[s][7] = b1[3];
+                    }
+                }
+                auto addends = [&](int r_uniform, int c_uniform, f32x4& lo, f32x4& hi) {
+                    if constexpr (ADD) {
+                        const float* a = add_lane + r_uniform * kPartialSide + c_uniform;
+                        for (int k = 0; k < add.count; ++k, a += kPartialTile) {
+                            lo += *reinterpret_cast<const f32x4*>(a);
+                            hi += *reinterpret_cast<const f32x4*>(a + 4);
+                        }
+                    }
+                };
+                if constexpr (OUT == DT_F32) {
+                    char* lane_base = c_problem + (m_wave + (lane & 15)) * row_bytes + static_cast<int64_t>(n_lane) * 4;
+                    wg::drain_pairs<MT, NT>(wv, acc, [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
+                        addends(r_uniform, c_uniform, lo, hi);
+                        grid::finish_run<OUT, BIAS>(lane_base + r_uniform * row_bytes + c_uniform * 4, p.alpha, bias[BIAS ? c_uniform / 32 : 0], lo, hi);
+                    });
+                } else {
+                    char* wave_base = c_problem + m_wave * row_bytes + static_cast<int64_t>(n_wave) * 2;
+                    wg::drain_rows<MT, NT>(
+                        wv, acc, patch, lane,
+                        [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
+                            addends(r_uniform, c_uniform, lo, hi);
+                            return grid::pack_run<OUT, BIAS>(p.alpha, bias[BIAS ? c_uniform / 32 : 0], lo, hi);
+                        },
+                        [&](int r_uniform, int r_lane, int byte_in_row, u32x4 piece) {
+                            __builtin_nontemporal_store(piece, reinterpret_cast<u32x4*>(wave_base + (r_uniform + r_lane) * row_bytes + byte_in_row));
+                        });
+                }
+            };
+            out_type([&](auto out_c) {
+                if (p.bias) run(out_c, std::true_type{});
+                else run(out_c, std::false_type{});
+            });
+            return;
+        }
+    }
+    if constexpr (PAIRED) {
+        if (p.split_k > 1 && inside && p.p_vec) {  // raw partial sums of a K slice, the same way
+            float* slab = p.partial + (static_cast<int64_t>(q.batch) * p.split_k + q.slice) * p.M * p.N;
+            float* lane_base = slab + static_cast<int64_t>(m_wave + (lane & 15)) * p.N + n_wave + 8 * (lane >> 4);
+            wg::drain_pairs<MT, NT>(wv, acc, [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
+                float* dst = lane_base + static_cast<int64_t>(r_uniform) * p.N + c_uniform;
+                *reinterpret_cast<f32x4*>(dst) = lo;
+                *reinterpret_cast<f32x4*>(dst + 4) = hi;
+            });
+            return;
+        }
+    }
     auto drain_any = [&](auto&& sink) {
-        if constexpr (OWN_PATCH) wg::drain<MT, NT, 16, 0>(wv, acc, patch, lane, sink);
-        else wg::drain<MT, NT>(wv, acc, patch, lane, sink);
+        if constexpr (OWN_PATCH) wg::drain<MT, NT, 16, 0, PAIRED>(wv, acc, patch, lane, sink);
+        else wg::drain<MT, NT, wg::kDrainRows, 4, PAIRED>(wv, acc, patch, lane, sink);
     };
     if (p.split_k > 1) {
         float* slab = p.partial + (static_cast<int64_t>(q.batch) * p.split_k + q.slice) * p.M * p.N;
         drain_any([&](int r, int c, f32x4 v) { grid::partial4(p, slab, m_wave + r, n_wave + c, v); });
         return;
     }
-    const int esize = p.c_dtype == DT_F32 ? 4 : 2;
-    char* c_problem = p.C + static_cast<int64_t>(q.batch) * p.batch_c * esize;
-    const bool inside = m_wave + lane::kBlock * MT <= p.M && n_wave + lane::kBlock * NT <= p.N;
-    if (inside && p.c_vec8 && p.beta == 0.0f && !(p.bias && p.bias_along_m)) {
-        // Common case: whole wave tile inside C, aligned rows, nothing to read back.
-        const int n_run = n_wave + 8 * (lane % (2 * NT));
-        float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (p.bias) {
-            const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + n_run);
-            const f32x4 b1 = *reinterpret_cast<const f32x4*>(p.bias + n_run + 4);
-            bias[0] = b0[0]; bias[1] = b0[1]; bias[2] = b0[2]; bias[3] = b0[3];
-            bias[4] = b1[0]; bias[5] = b1[1]; bias[6] = b1[2]; bias[7] = b1[3];
+    if constexpr (!PAIRED) {
+        if (fast) {
+            // Common case for the plain column order: the accumulators pass through the patch and
+            // come back as runs of eight consecutive n.
+            const int n_run = n_wave + 8 * (lane % (2 * NT));
+            float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (p.bias) {
+                const f32x4 b0 = *reinterpret_cast<const f32x4*>(p.bias + n_run);
+                const f32x4 b1 = *reinterpret_cast<const f32x4*>(p.bias + n_run + 4);
+                bias[0] = b0[0]; bias[1] = b0[1]; bias[2] = b0[2]; bias[3] = b0[3];
+                bias[4] = b1[0]; bias[5] = b1[1]; bias[6] = b1[2]; bias[7] = b1[3];
+            }
+            // the bias must be in registers before the first store is issued: stores and loads
+            // share one in-order counter, so a later wait for the bias would wait for stores too
+            wg::wait_counts<0, 15>();
+            const int64_t row_bytes = p.ldc * esize;
+            char* lane_base = c_problem + m_wave * row_bytes + static_cast<int64_t>(n_run) * esize;
+            out_type([&](auto out_c) {
+                constexpr int OUT = decltype(out_c)::value;
+                auto sink = [&](int r_uniform, int r_lane, f32x4 lo, f32x4 hi) {
+                    grid::finish_run<OUT, true>(lane_base + (r_uniform + r_lane) * row_bytes, p.alpha, bias, lo, hi);
+                };
+                if constexpr (OWN_PATCH) wg::drain_runs16<MT, NT>(wv, acc, patch, lane, sink);
+                else wg::drain_runs<MT, NT>(wv, acc, patch, lane, sink);
+            });
+            return;
         }
-        // the bias must be in registers before the first store is issued: stores and loads
-        // share one in-order counter, so a later wait for the bias would wait for stores too
-        wg::wait_counts<0, 15>();
-        const int64_t row_bytes = p.ldc * esize;
-        char* tile_base = c_problem + m_wave * row_bytes;                       // uniform
-        const uint32_t lane_off = static_cast<uint32_t>(n_run * esize);         // per lane, plus its row below
-        auto run = [&](auto out_c) {
-            constexpr int OUT = decltype(out_c)::value;
-            auto sink = [&](int r_uniform, int r_lane, f32x4 lo, f32x4 hi) {
-                char* row = tile_base + r_uniform * row_bytes;
-                if (add.count) {
-                    const float* a = add.first + (m_wave - q.m0 + r_uniform + r_lane) * kPartialSide + (n_run - q.n0);
-                    for (int k = 0; k < add.count; ++k, a += kPartialTile) {
-                        lo += *reinterpret_cast<const f32x4*>(a);
-                        hi += *reinterpret_cast<const f32x4*>(a + 4);
-                    }
-                }
-                grid::finish_run<OUT>(row + (lane_off + static_cast<uint32_t>(r_lane) * static_cast<uint32_t>(row_bytes)),
-                                      p.alpha, bias, lo, hi);
-            };
-            if constexpr (OWN_PATCH) wg::drain_runs16<MT, NT>(wv, acc, patch, lane, sink);
-            else wg::drain_runs<MT, NT>(wv, acc, patch, lane, sink);
-        };
-        if (p.c_dtype == DT_BF16) run(std::integral_constant<int, DT_BF16>{});
-        else if (p.c_dtype == DT_F16) run(std::integral_constant<int, DT_F16>{});
-        else run(std::integral_constant<int, DT_F32>{});
-        return;
     }
     drain_any([&](int r, int c, f32x4 v) {
-        const float* a = add.first + (m_wave - q.m0 + r) * kPartialSide + (n_wave - q.n0 + c);
-        for (int k = 0; k < add.count; ++k, a += kPartialTile) v += *reinterpret_cast<const f32x4*>(a);
+        if constexpr (ADD) {
+            const float* a = add.first + (m_wave - q.m0 + r) * kPartialSide + (n_wave - q.n0 + c);
+            for (int k = 0; k < add.count; ++k, a += kPartialTile) v += *reinterpret_cast<const f32x4*>(a);
+        }
         grid::finish4_any(p, c_problem, m_wave + r, n_wave + c, v);
     });
 }
 
-// One wave's accumulators into a row-major 256 x 256 fp32 tile (`slot`), as rows of eight
-// consecutive n through the wave's private LDS patch.  row0 / col0: the wave tile's place.
+// One wave's accumulators (paired block columns) into a row-major 256 x 256 fp32 tile (`slot`),
+// as runs of eight consecutive n straight from the registers.  row0 / col0: the wave tile's place.
 template <typename TileT, int MT, int NT>
-__device__ __forceinline__ void store_partial_tile(persp::Wave wv, const TileT& acc, char* patch, int lane, float* slot,
-                                                   int row0, int col0)
+__device__ __forceinline__ void store_partial_tile(persp::Wave wv, const TileT& acc, int lane, float* slot, int row0, int col0)
 {
-    float* base = slot + row0 * kPartialSide + col0 + 8 * (lane % (2 * NT));
-    wg::drain_runs16<MT, NT>(wv, acc, patch, lane, [&](int r_uniform, int r_lane, f32x4 lo, f32x4 hi) {
-        float* dst = base + (r_uniform + r_lane) * kPartialSide;
+    float* base = slot + (row0 + (lane & 15)) * kPartialSide + col0 + 8 * (lane >> 4);
+    wg::drain_pairs<MT, NT>(wv, acc, [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
+        float* dst = base + r_uniform * kPartialSide + c_uniform;
         *reinterpret_cast<f32x4*>(dst) = lo;
         *reinterpret_cast<f32x4*>(dst + 4) = hi;
     });
@@ -161,8 +229,12 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
     P::run(wgp, acc, a_tile, a_ld, a_rows, b_tile, b_ld, b_rows,
            (q.k_end - q.k_begin) / P::K_PER_STEP, lds, wave, lane);
 
-    epilogue<typename P::tile_t, P::MT, P::NT>(wgp, p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
-                                               q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane);
+    // The epilogue's per-lane addressing is computed after the K loop: kept live across it, it
+    // would not fit in registers beside the accumulators and fragments.
+    int lane_now = lane;
+    asm volatile("" : "+v"(lane_now));
+    epilogue<typename P::tile_t, P::MT, P::NT, false, P::PAIRED_N>(wgp, p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
+                                                                   q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane_now);
 }
 
 // Persistent form for the 256x256x64 tile: workgroup w takes tiles w, w + gridDim.x, ...
@@ -203,9 +275,9 @@ __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const
             // the K loop it would not fit in registers beside the accumulators and fragments.
             int lane_now = lane;
             asm volatile("" : "+v"(lane_now));
-            epilogue<typename P::tile_t, P::MT, P::NT, true>(wgp, p, cur, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
-                                                             cur.n0 + (wave % P::WAVES_N) * P::WTN,
-                                                             lds + P::PATCH_BASE + wave * P::PATCH_BYTES, wave, lane_now);
+            epilogue<typename P::tile_t, P::MT, P::NT, true, P::PAIRED_N>(wgp, p, cur, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
+                                                                          cur.n0 + (wave % P::WAVES_N) * P::WTN,
+                                                                          lds + P::PATCH_BASE + wave * P::PATCH_BYTES, wave, lane_now);
         },
         [&]() {
             cur = nxt;
@@ -306,7 +378,7 @@ __global__ __launch_bounds__(256) void gemm_streamk(const GemmParams p)
             const int row0 = (wave / P::WAVES_N) * P::WTM, col0 = (wave % P::WAVES_N) * P::WTN;
             if (cur.k1 < ksteps) {
                 // the tile is finished by a higher ticket: hand the partial sums over
-                store_partial_tile<typename P::tile_t, P::MT, P::NT>(wgp.wave(), acc, patch, lane_now, my_slot, row0, col0);
+                store_partial_tile<typename P::tile_t, P::MT, P::NT>(wgp.wave(), acc, lane_now, my_slot, row0, col0);
                 __threadfence();
                 wg::sync(wgp);
                 if (threadIdx.x == 0) __hip_atomic_store(flags + slot, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -332,9 +404,9 @@ __global__ __launch_bounds__(256) void gemm_streamk(const GemmParams p)
             }
             Placement q;
             q.batch = 0; q.slice = 0; q.m0 = cur.m0; q.n0 = cur.n0; q.k_begin = 0; q.k_end = p.K;
-            epilogue<typename P::tile_t, P::MT, P::NT, true>(wgp, p, q, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
-                                                             cur.n0 + (wave % P::WAVES_N) * P::WTN,
-                                                             patch, wave, lane_now, add);
+            epilogue<typename P::tile_t, P::MT, P::NT, true, P::PAIRED_N, true>(wgp, p, q, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
+                                                                                cur.n0 + (wave % P::WAVES_N) * P::WTN,
+                                                                                patch, wave, lane_now, add);
         },
         [&]() {
             stop -= cur.k1 - cur.k0;

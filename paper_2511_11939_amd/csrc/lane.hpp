@@ -101,6 +101,25 @@ __device__ __forceinline__ typename Frag<T>::type load_fragment_at(persp::Lane, 
 __host__ __device__ constexpr int acc_row(int reg, int lane) { return 4 * (lane >> 4) + reg; }
 __host__ __device__ constexpr int acc_col(int lane) { return lane & 15; }
 
+// ---- pairing the columns of neighbouring blocks --------------------------------------
+// A lane's four accumulators of a block are four consecutive columns; a 16-bit result wants
+// eight per 16-byte store.  When the rows of the "row" operand's tile are dealt to LDS rows so
+// that LDS row 32s + 16h + 4a + b holds tile row 32s + 8a + 4h + b (h in 0..1, a and b in 0..3),
+// block column j = 2s + h hands lane l the columns 32s + 8(l/16) + 4h .. +3: the two blocks of
+// a pair give every lane eight consecutive columns, and the four lanes that share a row 64
+// contiguous bytes of a 16-bit result, straight from the accumulator registers.  The copies
+// move whole 128-byte rows, so dealing the rows differently costs nothing.
+__host__ __device__ constexpr int paired_tile_row(int lds_row)
+{
+    return (lds_row & ~31) | ((lds_row & 12) << 1) | ((lds_row & 16) >> 2) | (lds_row & 3);
+}
+// First of the four columns (relative to the wave tile) that lane `lane` holds of block column j.
+template <bool PAIRED>
+__host__ __device__ constexpr int acc_first_col(int j, int lane)
+{
+    return PAIRED ? 32 * (j >> 1) + 8 * (lane >> 4) + 4 * (j & 1) : kBlock * j + 4 * (lane >> 4);
+}
+
 // ---- output conversion ---------------------------------------------------------
 __device__ __forceinline__ uint16_t to_bf16_bits(float x)
 {

@@ -83,7 +83,7 @@ constexpr int drain_patch_bytes(int nt) { return kDrainRows * (lane::kBlock * nt
 
 // ROWS: rows per pass (32 = two blocks, 16 = one); PAD: floats of row padding (4 keeps the
 // accesses free of bank conflicts, 0 fits 16 rows of a 128-wide tile into 8 KiB).
-template <int MT, int NT, int ROWS = kDrainRows, int PAD = 4, typename TileT, typename Sink>
+template <int MT, int NT, int ROWS = kDrainRows, int PAD = 4, bool PAIRED = false, typename TileT, typename Sink>
 __device__ __forceinline__ void drain(persp::Wave, const TileT& acc, char* patch, int lane, Sink&& sink)
 {
     static_assert(ROWS == 16 || (ROWS == 32 && MT % 2 == 0), "a pass takes one or two 16-row blocks");
@@ -99,9 +99,10 @@ __device__ __forceinline__ void drain(persp::Wave, const TileT& acc, char* patch
     for (int pass = 0; pass < MT / BLOCKS; ++pass) {
 #pragma unroll
         for (int ii = 0; ii < BLOCKS; ++ii) {
-            float* wr = buf + (lane::kBlock * ii + lane::acc_col(lane)) * PITCH + lane::acc_row(0, lane);
+            float* wr = buf + (lane::kBlock * ii + lane::acc_col(lane)) * PITCH;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) *reinterpret_cast<f32x4*>(wr + lane::kBlock * j) = acc.acc[BLOCKS * pass + ii][j];
+            for (int j = 0; j < NT; ++j)
+                *reinterpret_cast<f32x4*>(wr + lane::acc_first_col<PAIRED>(j, lane)) = acc.acc[BLOCKS * pass + ii][j];
         }
         const int col = 4 * (lane % LANES_PER_ROW);
 #pragma unroll 4
@@ -155,6 +156,65 @@ __device__ __forceinline__ void drain_runs(persp::Wave, const TileT& acc, char* 
     }
 }
 
+// Drain without LDS for a wave tile whose block columns are paired (lane::paired_tile_row):
+// every lane already holds runs of eight consecutive n.  sink(row_uniform, col_uniform, lo, hi)
+// receives the run of row row_uniform + lane % 16, columns col_uniform + 8 * (lane / 16) .. +7
+// of the wave tile, once for every block row and pair of block columns.
+template <int MT, int NT, typename TileT, typename Sink>
+__device__ __forceinline__ void drain_pairs(persp::Wave, const TileT& acc, Sink&& sink)
+{
+    static_assert(NT % 2 == 0, "block columns come in pairs");
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int s = 0; s < NT / 2; ++s) {
+            // (taken from the accumulation registers here and no earlier: without this the moves
+            // of all blocks drift to the top of the epilogue and spill)
+            f32x4 lo = acc.acc[i][2 * s], hi = acc.acc[i][2 * s + 1];
+            asm volatile("" : "+a"(lo), "+a"(hi));
+            sink(lane::kBlock * i, 32 * s, lo, hi);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // one block row at a time keeps the register need small
+    }
+}
+
+// Drain for a 16-bit result of a wave tile with paired block columns.  Every lane finishes its
+// runs of eight consecutive n itself: pack(row_uniform, col_uniform, lo, hi) returns the 16
+// bytes of the run of row row_uniform + lane % 16, columns col_uniform + 8 * (lane / 16) .. +7.
+// The pieces of one block row (16 rows of 32 * NT bytes) pass through the wave's LDS patch and
+// come back row by row, so that store(row_uniform, row_lane, byte_in_row, piece) writes whole
+// rows of the wave tile (16 consecutive lanes hold 256 contiguous bytes).  Four times less LDS
+// traffic than draining the fp32 accumulators, and full cache lines per store instruction.
+// `patch` is this wave's, kRowsPatchBytes(NT) long; the padding of 16 bytes per row spreads
+// both the writes (16 rows, one piece each) and the reads over all banks.
+constexpr int rows_patch_bytes(int nt) { return lane::kBlock * (2 * lane::kBlock * nt + 16); }
+template <int MT, int NT, typename TileT, typename Pack, typename Store>
+__device__ __forceinline__ void drain_rows(persp::Wave, const TileT& acc, char* patch, int lane, Pack&& pack, Store&& store)
+{
+    static_assert(NT % 2 == 0, "block columns come in pairs");
+    constexpr int ROW_BYTES = 2 * lane::kBlock * NT, PITCH = ROW_BYTES + 16;
+    constexpr int PIECES = ROW_BYTES / 16;        // lanes that share a row on the way out
+    constexpr int ROWS_PER_ITER = 64 / PIECES, ITERS = lane::kBlock / ROWS_PER_ITER;
+    char* wr = patch + (lane & 15) * PITCH + 16 * (lane >> 4);
+    const int piece = lane % PIECES, sub = lane / PIECES;
+    const char* rd = patch + sub * PITCH + 16 * piece;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int s = 0; s < NT / 2; ++s) {
+            f32x4 lo = acc.acc[i][2 * s], hi = acc.acc[i][2 * s + 1];
+            asm volatile("" : "+a"(lo), "+a"(hi));  // taken from the accumulation registers here and no earlier
+            *reinterpret_cast<u32x4*>(wr + 64 * s) = pack(lane::kBlock * i, 32 * s, lo, hi);
+        }
+        u32x4 out[ITERS];
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) out[it] = *reinterpret_cast<const u32x4*>(rd + it * ROWS_PER_ITER * PITCH);
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) store(lane::kBlock * i + it * ROWS_PER_ITER, sub, 16 * piece, out[it]);
+        __builtin_amdgcn_sched_barrier(0);  // one block row at a time keeps the register need small
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // Pipelined main loop: direct-to-LDS copies, STAGES slots.  An operand is K-contiguous
 // (its LDS tile is BM or BN rows of BK elements) or contiguous along its other index
@@ -172,6 +232,9 @@ struct Pipeline {
     static_assert(!B_KN || (BK == 64 && BN == 128), "n-contiguous B: k-rows of 128 elements");
     static_assert(!A_MK || (BK == 64 && BM == 128), "m-contiguous A: k-rows of 128 elements");
     static_assert(!(A_MK && B_KN) || BM == BN, "both operands as k-rows: square tile");
+    // A K-contiguous B is dealt to the LDS rows in the paired order (lane::paired_tile_row), so
+    // that the epilogue can store from the registers; the k-row form keeps the plain order.
+    static constexpr bool PAIRED_N = !B_KN;
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -252,7 +315,7 @@ struct Pipeline {
 #pragma unroll
         for (int i = 0; i < B_COPIES; ++i) {
             if constexpr (!B_KN) {
-                int row = (i * NW + wave) * COPY_ROWS + sub_row;
+                int row = lane::paired_tile_row((i * NW + wave) * COPY_ROWS + sub_row);
                 row = row < b_rows ? row : b_rows - 1;
                 g_off[A_COPIES + i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
             } else {
@@ -426,6 +489,7 @@ struct Pipeline {
         int t = 0;
         if (ksteps == 1) {
             k_step(no{}, no{}, yes{}, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
             return;
         }
         if (ksteps > 2) k_step(no{}, yes{}, no{}, 0, 0, 1);
@@ -445,6 +509,7 @@ struct Pipeline {
             ++t;
         }
         k_step(no{}, no{}, yes{}, t, t & 1, t & 1);
+        __builtin_amdgcn_sched_barrier(0);  // nothing of the epilogue moves up into the K loop
     }
 };
 
@@ -503,6 +568,7 @@ template <typename T, int HEADN = 0>  // copies of a step left for the start of 
 struct PersistentPipe {
     using L = lane::TileLayout<64>;
     static constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2, NW = 4, THREADS = 256;
+    static constexpr bool PAIRED_N = true;  // B rows in the paired order, as in Pipeline
     static constexpr int WTM = 128, WTN = 128, MT = WTM / lane::kBlock, NT = WTN / lane::kBlock;
     static constexpr int KSUB = BK / lane::kBlockK, NM = MT * NT, NR = MT + NT;
     static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -548,9 +614,9 @@ struct PersistentPipe {
             const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
 #pragma unroll
             for (int i = 0; i < A_COPIES; ++i) {
-                const int row = (i * NW + wave) * COPY_ROWS + sub_row;
+                const int row = (i * NW + wave) * COPY_ROWS + sub_row, row_b = lane::paired_tile_row(row);
                 const int ra = row < s.a_rows ? row : s.a_rows - 1;
-                const int rb = row < s.b_rows ? row : s.b_rows - 1;
+                const int rb = row_b < s.b_rows ? row_b : s.b_rows - 1;
                 g_off[i] = static_cast<uint32_t>(ra) * s.a_ld + chunk * lane::kChunkBytes;
                 g_off[A_COPIES + i] = static_cast<uint32_t>(rb) * s.b_ld + chunk * lane::kChunkBytes;
             }
