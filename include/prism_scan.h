@@ -55,6 +55,27 @@ PRISM_API prism_status_t prism_scan_u32(const uint32_t* in, uint32_t* out, int64
                                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same scan for callers that can neither allocate nor bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The status words live
+ * in an array that is part of the library's code object (512 KiB + 64 bytes, held by every GPU
+ * the library runs on until the process ends); the call allocates and frees nothing.
+ *
+ * in, out, n, hip_stream   as prism_scan_u32, with n <= 2^30; a larger n is refused with
+ *              PRISM_ERR_WORKSPACE (use prism_scan_u32 with a workspace of your own).
+ * gave_up      device, 4-byte aligned, or NULL: a word that the call clears and that a look-back
+ *              which gave up waiting sets to 1 (what prism_scan_check reads from a workspace);
+ *              the caller reads it after the stream has executed the work.
+ *
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and give wrong results; calls on one stream, or otherwise
+ * ordered, are fine, and each call clears what it needs with a kernel of its own (no memset
+ * node, so the call can be captured).  The first call on a GPU looks the array's device
+ * address up (hipGetSymbolAddress, once per GPU): make that call outside graph capture.
+ */
+PRISM_API prism_status_t prism_scan_u32_static(const uint32_t* in, uint32_t* out, int64_t n,
+                                               uint32_t* gave_up, void* hip_stream);
+
+/*
  * Synchronises the stream and reads the workspace's error word back:
  * PRISM_OK, or PRISM_ERR_LAUNCH when a look-back of the last scan that used
  * this workspace gave up waiting.

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     prism_gemm, prism_gemm_batched, prism_gemm_workspace_size, prism_gemm_plan,
     prism_sched_map, prism_status_string, prism_version,
     gemm, make_desc,
-    prism_scan_workspace_size, prism_scan_u32, prism_scan_check, scan_u32,
+    prism_scan_workspace_size, prism_scan_u32, prism_scan_check, prism_scan_u32_static, scan_u32,
 )

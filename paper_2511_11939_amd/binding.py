@@ -103,6 +103,8 @@ def load_library():
     lib.prism_scan_u32.restype = ctypes.c_int
     lib.prism_scan_check.argtypes = [vp, vp]
     lib.prism_scan_check.restype = ctypes.c_int
+    lib.prism_scan_u32_static.argtypes = [vp, vp, i64, vp, vp]
+    lib.prism_scan_u32_static.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -227,6 +229,10 @@ def prism_scan_u32(inp, out, n, workspace, workspace_bytes, hip_stream=None) -> 
 
 def prism_scan_check(workspace, hip_stream=None) -> int:
     return load_library().prism_scan_check(_p(workspace), _p(hip_stream))
+
+
+def prism_scan_u32_static(inp, out, n, gave_up=None, hip_stream=None) -> int:
+    return load_library().prism_scan_u32_static(_p(inp), _p(out), n, _p(gave_up), _p(hip_stream))
 
 
 def scan_u32(inp, out, n, workspace, *, stream=None):

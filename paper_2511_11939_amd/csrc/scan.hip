@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <mutex>
 
 #include "../../include/prism_scan.h"
 #include "persp.hpp"
@@ -102,16 +103,19 @@ __device__ __forceinline__ uint32_t look_back(persp::Wave, const uint64_t* statu
     }
 }
 
-__global__ __launch_bounds__(64) void scan_init(uint32_t* header, uint64_t* status, int64_t tiles)
+// Clears what a scan needs cleared: the header, one status word per tile and the error word
+// (the header's own, or a word of the caller's).
+__global__ __launch_bounds__(64) void scan_init(uint32_t* header, uint64_t* status, int64_t tiles, uint32_t* error_word)
 {
     const int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
     if (i < tiles) status[i] = pack(kInvalid, 0);
     if (i < static_cast<int64_t>(kHeaderBytes / 4)) header[i] = 0u;
+    if (i == 0) *error_word = 0u;
 }
 
 template <bool VEC_IN, bool VEC_OUT>
 __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_t* out, int64_t n, uint32_t* header,
-                                                     uint64_t* status, uint32_t spin_limit)
+                                                     uint64_t* status, uint32_t spin_limit, uint32_t* error_word)
 {
     const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
     const persp::Wave wv = wgp.wave();
@@ -176,7 +180,7 @@ __global__ __launch_bounds__(256) void scan_lookback(const uint32_t* in, uint32_
         } else {
             if (lane == 0)
                 __hip_atomic_store(status + tile, pack(kAggregate, aggregate), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            exclusive = look_back(wv, status, tile, lane, spin_limit, header + 1);
+            exclusive = look_back(wv, status, tile, lane, spin_limit, error_word);
             if (lane == 0)
                 __hip_atomic_store(status + tile, pack(kPrefix, exclusive + aggregate), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -216,6 +220,71 @@ uint32_t spin_limit()
     return v < 0 ? 0u : static_cast<uint32_t>(v);
 }
 
+// in / out of a non-empty scan: present, 4-byte aligned, the same array or disjoint ones.
+prism_status_t check_data(const uint32_t* in, const uint32_t* out, int64_t n)
+{
+    if (!in || !out || !aligned_to(in, 4) || !aligned_to(out, 4)) return PRISM_ERR_INVALID_ARG;
+    if (in != out) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
+        const uintptr_t bytes = static_cast<uintptr_t>(n) * 4;
+        if (a < b + bytes && b < a + bytes) return PRISM_ERR_INVALID_ARG;
+    }
+    return PRISM_OK;
+}
+
+bool shares_memory(const void* w, size_t w_bytes, const uint32_t* data, int64_t n)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(w), b = reinterpret_cast<uintptr_t>(data);
+    return a < b + static_cast<uintptr_t>(n) * 4 && b < a + w_bytes;
+}
+
+// The two launches of a scan: clear the workspace (a kernel, so that the call can be captured
+// into a graph), then the single pass.  `workspace` holds the header and the status words.
+prism_status_t enqueue(const uint32_t* in, uint32_t* out, int64_t n, void* workspace, uint32_t* error_word, hipStream_t stream)
+{
+    using namespace prism::scan;
+    const int64_t tiles = (n + kTile - 1) / kTile;
+    uint32_t* header = static_cast<uint32_t*>(workspace);
+    uint64_t* status = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + kHeaderBytes);
+    const int64_t init_items = tiles > 16 ? tiles : 16;
+    hipLaunchKernelGGL(scan_init, dim3(static_cast<unsigned>((init_items + 63) / 64)), dim3(64), 0, stream, header, status,
+                       tiles, error_word);
+    if (hipGetLastError() != hipSuccess) return PRISM_ERR_LAUNCH;
+    const bool vin = aligned_to(in, 16), vout = aligned_to(out, 16);
+    const dim3 grid(static_cast<unsigned>(tiles)), block(kThreads);
+    const uint32_t limit = spin_limit();
+    if (vin && vout) hipLaunchKernelGGL((scan_lookback<true, true>), grid, block, 0, stream, in, out, n, header, status, limit, error_word);
+    else if (vin) hipLaunchKernelGGL((scan_lookback<true, false>), grid, block, 0, stream, in, out, n, header, status, limit, error_word);
+    else if (vout) hipLaunchKernelGGL((scan_lookback<false, true>), grid, block, 0, stream, in, out, n, header, status, limit, error_word);
+    else hipLaunchKernelGGL((scan_lookback<false, false>), grid, block, 0, stream, in, out, n, header, status, limit, error_word);
+    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_ERR_LAUNCH;
+}
+
+// ---- the scratch of prism_scan_u32_static ---------------------------------------------------
+// One array per GPU, part of the loaded code object, for callers that must not allocate.  Its
+// name is only a host-side handle: the address a kernel can use is asked for once per device,
+// with that device current, and kept; every later use goes through the kept pointer.
+constexpr int64_t kStaticMaxN = int64_t{1} << 30;
+constexpr size_t kStaticScratchBytes = prism::scan::kHeaderBytes + static_cast<size_t>(kStaticMaxN / prism::scan::kTile) * sizeof(uint64_t);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_of_device[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+void* static_scratch_of_current_device()
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_of_device[device]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_scratch_of_device[device] = ptr;
+    }
+    return g_scratch_of_device[device];
+}
+
 }  // namespace
 
 extern "C" {
@@ -236,36 +305,27 @@ prism_status_t prism_scan_u32(const uint32_t* in, uint32_t* out, int64_t n, void
     size_t need = 0;
     if (prism_scan_workspace_size(n, &need) != PRISM_OK) return PRISM_ERR_INVALID_ARG;
     if (n == 0) return PRISM_OK;
-    if (!in || !out || !aligned_to(in, 4) || !aligned_to(out, 4)) return PRISM_ERR_INVALID_ARG;
-    if (in != out) {
-        const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
-        const uintptr_t bytes = static_cast<uintptr_t>(n) * 4;
-        if (a < b + bytes && b < a + bytes) return PRISM_ERR_INVALID_ARG;
-    }
+    const prism_status_t bad = check_data(in, out, n);
+    if (bad != PRISM_OK) return bad;
     if (!workspace || workspace_bytes < need) return PRISM_ERR_WORKSPACE;
     if (!aligned_to(workspace, 8)) return PRISM_ERR_INVALID_ARG;
-    {   // the workspace must not share memory with the data
-        const uintptr_t w = reinterpret_cast<uintptr_t>(workspace), bytes = static_cast<uintptr_t>(n) * 4;
-        const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
-        if ((w < a + bytes && a < w + need) || (w < b + bytes && b < w + need)) return PRISM_ERR_INVALID_ARG;
-    }
+    if (shares_memory(workspace, need, in, n) || shares_memory(workspace, need, out, n)) return PRISM_ERR_INVALID_ARG;
+    return enqueue(in, out, n, workspace, static_cast<uint32_t*>(workspace) + 1, static_cast<hipStream_t>(hip_stream));
+}
 
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int64_t tiles = (n + kTile - 1) / kTile;
-    uint32_t* header = static_cast<uint32_t*>(workspace);
-    uint64_t* status = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + kHeaderBytes);
-    const int64_t init_items = tiles > 16 ? tiles : 16;
-    hipLaunchKernelGGL(scan_init, dim3(static_cast<unsigned>((init_items + 63) / 64)), dim3(64), 0, stream, header, status,
-                       tiles);
-    if (hipGetLastError() != hipSuccess) return PRISM_ERR_LAUNCH;
-    const bool vin = aligned_to(in, 16), vout = aligned_to(out, 16);
-    const dim3 grid(static_cast<unsigned>(tiles)), block(kThreads);
-    const uint32_t limit = spin_limit();
-    if (vin && vout) hipLaunchKernelGGL((scan_lookback<true, true>), grid, block, 0, stream, in, out, n, header, status, limit);
-    else if (vin) hipLaunchKernelGGL((scan_lookback<true, false>), grid, block, 0, stream, in, out, n, header, status, limit);
-    else if (vout) hipLaunchKernelGGL((scan_lookback<false, true>), grid, block, 0, stream, in, out, n, header, status, limit);
-    else hipLaunchKernelGGL((scan_lookback<false, false>), grid, block, 0, stream, in, out, n, header, status, limit);
-    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_ERR_LAUNCH;
+prism_status_t prism_scan_u32_static(const uint32_t* in, uint32_t* out, int64_t n, uint32_t* gave_up, void* hip_stream)
+{
+    using namespace prism::scan;
+    if (n < 0) return PRISM_ERR_INVALID_ARG;
+    if (n > kStaticMaxN) return PRISM_ERR_WORKSPACE;  // beyond what the built-in scratch holds
+    if (n == 0) return PRISM_OK;
+    const prism_status_t bad = check_data(in, out, n);
+    if (bad != PRISM_OK) return bad;
+    if (gave_up && !aligned_to(gave_up, 4)) return PRISM_ERR_INVALID_ARG;
+    if (gave_up && (shares_memory(gave_up, 4, in, n) || shares_memory(gave_up, 4, out, n))) return PRISM_ERR_INVALID_ARG;
+    void* ws = static_scratch_of_current_device();
+    if (!ws) return PRISM_ERR_LAUNCH;
+    return enqueue(in, out, n, ws, gave_up ? gave_up : static_cast<uint32_t*>(ws) + 1, static_cast<hipStream_t>(hip_stream));
 }
 
 prism_status_t prism_scan_check(const void* workspace, void* hip_stream)

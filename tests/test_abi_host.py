@@ -225,6 +225,14 @@ def test_scan_host_validation():
     assert P.prism_scan_u32(IN, OUT, 100, WS + 4, 1 << 20, None) == S.INVALID_ARG     # workspace alignment
     assert P.prism_scan_u32(IN, OUT, 100, IN + 64, 1 << 20, None) == S.INVALID_ARG    # workspace inside the data
     assert P.prism_scan_check(None, None) == S.INVALID_ARG
+    # the entry point with the built-in scratch: argument errors come before anything touches a GPU
+    assert P.prism_scan_u32_static(IN, OUT, (1 << 30) + 1, None, None) == S.WORKSPACE   # more than the scratch holds
+    assert P.prism_scan_u32_static(IN, OUT, -1, None, None) == S.INVALID_ARG
+    assert P.prism_scan_u32_static(None, None, 0, None, None) == S.OK
+    assert P.prism_scan_u32_static(None, OUT, 8, None, None) == S.INVALID_ARG
+    assert P.prism_scan_u32_static(IN, IN + 40, 100, None, None) == S.INVALID_ARG       # partial overlap
+    assert P.prism_scan_u32_static(IN, OUT, 100, IN + 2, None) == S.INVALID_ARG         # flag not 4-byte aligned
+    assert P.prism_scan_u32_static(IN, OUT, 100, IN + 8, None) == S.INVALID_ARG         # flag inside the data
 
 
 def test_persistent_kernel_needs_an_even_number_of_k_steps():
