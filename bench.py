@@ -2,10 +2,13 @@
 """Throughput of the GEMM hot path (and of the sgemm and scan workloads) on one MI355X.
 
 A step is one call of prism_gemm(_batched) (or prism_scan_u32) on the named synthetic
-workload with the operands already resident in HBM.  Order of a run: untimed launches of
-the same step for --ramp-seconds (the GPU's clock governor needs about 0.1 s of load to
-reach the clock it sustains; reported as "clock_ramp"), then --warmup untimed steps, then
-exactly --steps timed steps between two events on the launch stream.  Prints one JSON line.
+workload with the operands already resident in HBM.  Order of a run: the paper's own short
+protocol first (5 warm-up + 10 timed launches on a GPU that has seen no load yet: "cold"); for
+a workload bound by the matrix pipe, the matrix instructions alone under the same protocol
+("mfma_probe": the ceiling and the clock they sustain on this machine); then untimed launches of
+the step for --ramp-seconds (the GPU's clock governor needs about 0.1 s of load to reach the
+clock it sustains; "clock_ramp"), --warmup untimed steps, and exactly --steps timed steps
+between two events on the launch stream.  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -38,7 +41,9 @@ def source_digest() -> str:
     import glob
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2511_11939_amd", "csrc", "*"))):
+    files = [f for f in glob.glob(os.path.join(ROOT, "paper_2511_11939_amd", "csrc", "*"))
+             if f.endswith((".hip", ".hpp"))]          # sources only: objects differ from build to build
+    for f in sorted(files):
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
@@ -72,6 +77,46 @@ def clock_ramp(step, seconds: float) -> int:
         torch.cuda.synchronize()
         n += 50
     return n
+
+
+def mfma_probe(ab_dtype: str, iterations: int, ramp_seconds: float, launches: int = 20) -> dict:
+    """The matrix instructions alone (prism_mfma_probe: the GEMM's wave tile on register-resident
+    N(0,1) operands, `iterations` K steps per launch) under the same protocol as the GEMM: what they
+    sustain on this machine right now, and at which shader clock."""
+    import numpy as np
+    import torch
+    import paper_2511_11939_amd as P
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0x5EED00AA)
+    n = P.MFMA_PROBE_OPERAND_BYTES // (4 if ab_dtype == "f32" else 2)
+    vals = torch.randn(n, device="cuda", generator=g)
+    ops = vals if ab_dtype == "f32" else vals.to(torch.bfloat16 if ab_dtype == "bf16" else torch.float16)
+    counters = torch.zeros(P.MFMA_PROBE_COUNTER_BYTES // 8, dtype=torch.int64, device="cuda")
+    stream = torch.cuda.current_stream()
+    code = {"bf16": P.DType.BF16, "f16": P.DType.F16, "f32": P.DType.F32}[ab_dtype]
+
+    def step():
+        s = P.prism_mfma_probe(code, ops, P.MFMA_PROBE_OPERAND_BYTES, iterations, counters,
+                               P.MFMA_PROBE_COUNTER_BYTES, stream.cuda_stream)
+        assert s == 0, s
+
+    clock_ramp(step, ramp_seconds)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(launches):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    launch_s = e0.elapsed_time(e1) * 1e-3 / launches
+    c = counters.cpu().numpy().reshape(-1, 4)
+    cycles, ticks = float(c[:, 0].mean()), float(c[:, 1].mean())
+    flop = P.MFMA_PROBE_FLOP_PER_ITERATION * iterations * (0.5 if ab_dtype == "f32" else 1.0)
+    loop_s = ticks / 100e6
+    return {"tflops_loop": round(flop / loop_s / 1e12, 1), "tflops_launch": round(flop / launch_s / 1e12, 1),
+            "clock_mhz": round(cycles / ticks * 100.0, 0), "cycles_per_k_step": round(cycles / iterations, 1),
+            "iterations": iterations, "launch_us": round(launch_s * 1e6, 2),
+            "what": "matrix instructions only, N(0,1) operands in registers, 256 workgroups x 4 waves, "
+                    "after the same clock ramp; tflops_loop is inside the kernel's loop, tflops_launch per launch"}
 
 
 def copy_ceiling_gbs(n_bytes: int = 1 << 28, reps: int = 20) -> float:
@@ -183,6 +228,8 @@ def main() -> int:
     ap.add_argument("--ramp-seconds", type=float, default=0.3,
                     help="untimed launches of the same step before the warm-up steps, long enough for the "
                          "GPU's clock governor to reach its sustained state (0 = none)")
+    ap.add_argument("--no-mfma-probe", dest="mfma_probe", action="store_false",
+                    help="skip the matrix-instructions-only probe that is reported beside MFMA-bound workloads")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
                     help="run only a device copy of BYTES (counter calibration under rocprofv3)")
     args = ap.parse_args()
@@ -230,19 +277,32 @@ def main() -> int:
         P.gemm(A, B, C, M=w.M, N=w.N, K=w.K, desc=desc, batch=w.batch, strideA=w.M * w.K,
                strideB=w.K * w.N, strideC=w.M * w.N, stream=stream)
 
+    def timed(warmup: int, steps: int):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(steps):
+            step()
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ev0.elapsed_time(ev1)   # host wall seconds, device ms (events on the launch stream)
+
+    # The paper's own protocol (section 6: 5 warm-up launches, mean of 10 timed ones), first thing
+    # in the process, before the clock governor has seen any load: reported beside the sustained figure.
+    cold_wall, cold_ms = timed(5, 10)
+    cold = {"protocol": "5 warm-up + 10 timed launches, no clock ramp, first work of the process",
+            "ms_per_step": round(cold_wall * 1e3 / 10, 5), "launch_us": round(cold_ms * 1e3 / 10, 2),
+            "value": round(w.flops / (cold_wall / 10) / 1e12, 2), "unit": "TFLOP/s"}
+    probe = None
+    if args.mfma_probe and w.name != "cfg5_batched_512" and w.name != "cfg1_256_rowrow_f32":
+        es_k = 32 if w.ab_dtype == "f32" else 64
+        probe = mfma_probe(w.ab_dtype, max(1, w.K // es_k // max(1, plan.split_k)), args.ramp_seconds)
+
     ramp_launches = clock_ramp(step, args.ramp_seconds)
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(args.steps):
-        step()
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    dev_ms = ev0.elapsed_time(ev1)                  # events on the launch stream
+    wall, dev_ms = timed(args.warmup, args.steps)
 
     ms_per_step = wall * 1e3 / args.steps
     tflops = w.flops / (ms_per_step * 1e-3) / 1e12
@@ -258,6 +318,10 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
                     "device_copy_gbs": round(copy_ceiling_gbs(), 1)}
+    if probe is not None:
+        roofline["mfma_probe_tflops"] = probe["tflops_loop"]
+        roofline["mfma_probe_clock_mhz"] = probe["clock_mhz"]
+        roofline["frac_of_probe"] = round(achieved / probe["tflops_loop"], 4)
     roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent", 4: "gemm_streamk"}.get(plan.kernel, "none")
     roofline["launch_us"] = round(launch_ms * 1e3, 2)
     measured = MEASURED_TRAFFIC.get(w.name)
@@ -265,8 +329,9 @@ def main() -> int:
         roofline["traffic"] = measured[0]
 
     out = {
-        "metric": ("fp32 GEMM TFLOP/s and % of MI355X fp32 MFMA peak (1 GPU)" if w.ab_dtype == "f32" else
-                   "bf16 GEMM TFLOP/s and % of MI355X dense bf16 MFMA peak (1 GPU)"),
+        "metric": {"f32": "fp32 GEMM TFLOP/s and % of MI355X fp32 MFMA peak (1 GPU)",
+                   "f16": "fp16 GEMM TFLOP/s and % of MI355X dense fp16 MFMA peak (1 GPU)",
+                   "bf16": "bf16 GEMM TFLOP/s and % of MI355X dense bf16 MFMA peak (1 GPU)"}[w.ab_dtype],
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
@@ -278,7 +343,19 @@ def main() -> int:
         "pct_of_mfma_peak": round(100.0 * tflops / peak_mfma, 2),
         "roofline": roofline,
         "clock_ramp": {"seconds": args.ramp_seconds, "launches": ramp_launches},
+        "cold": cold,
     }
+    if probe is not None:
+        out["mfma_probe"] = probe
+    if plan.split_k > 1:
+        # A K split also moves the fp32 partial sums: written once by the slices, read once by
+        # the reduction.  With them counted the path is bound by memory, not by the matrix pipe.
+        ws_traffic = 2.0 * plan.split_k * w.batch * w.M * w.N * 4
+        hbm = (algorithmic_bytes(w) + ws_traffic) / (launch_ms * 1e-3) / 1e9
+        out["roofline_hbm"] = {"bound": "hbm", "achieved": round(hbm, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": round(hbm / PEAK_HBM_GBS, 4),
+                               "bytes": int(algorithmic_bytes(w) + ws_traffic),
+                               "what": "operands and result once, plus the split-K partial sums written and read once"}
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, on an evenly spread subset of output rows of problem 0

@@ -169,6 +169,31 @@ PRISM_API prism_status_t prism_gemm_plan(const prism_gemm_desc_t* d, int64_t M, 
 PRISM_API prism_status_t prism_sched_map(int64_t wg, int64_t tiles_m, int64_t tiles_n, int64_t units,
                                int64_t* tile_m, int64_t* tile_n, int64_t* unit);
 
+/*
+ * Measurement aid: the ceiling of the matrix instructions alone.  Launches 256 workgroups of
+ * four wavefronts that run the register-blocked wave tile of the GEMM kernels (8 x 8 blocks of
+ * 16 x 16, the MFMA of paper section 6.2's "collective matrix-core instructions") `iterations`
+ * times over operand fragments held in registers: no LDS and no memory traffic inside the
+ * loop.  One iteration is the matrix work of one K step of the 256 x 256 x 64 tile, so
+ * `iterations` = K / 64 mimics a GEMM's launch; a launch does
+ * PRISM_MFMA_PROBE_FLOP_PER_ITERATION * iterations floating-point operations (half of that
+ * for fp32 operands, whose K step is 32 elements).
+ *
+ * ab_dtype     BF16, F16 or F32: which matrix instruction.
+ * operands     device, 16-byte aligned, PRISM_MFMA_PROBE_OPERAND_BYTES bytes of operand values
+ *              (their distribution matters: the clock a GPU sustains depends on the data).
+ * counters     device, 8-byte aligned, PRISM_MFMA_PROBE_COUNTER_BYTES bytes; wave w of workgroup
+ *              g writes four uint64 at index 4 * (4 * g + w): shader-clock cycles of its loop,
+ *              ticks of the constant 100 MHz counter over the same span, a checksum, iterations.
+ * Too small a buffer is PRISM_ERR_WORKSPACE.  Enqueues on hip_stream; time it with events.
+ */
+#define PRISM_MFMA_PROBE_OPERAND_BYTES ((size_t)33554432)
+#define PRISM_MFMA_PROBE_COUNTER_BYTES ((size_t)32768)
+#define PRISM_MFMA_PROBE_FLOP_PER_ITERATION 2147483648.0 /* 256 x 4 waves x 128 MFMAs x 2 x 16 x 16 x 32 */
+PRISM_API prism_status_t prism_mfma_probe(int32_t ab_dtype, const void* operands, size_t operand_bytes,
+                                          int32_t iterations, uint64_t* counters, size_t counter_bytes,
+                                          void* hip_stream);
+
 /* Static string for a status code ("PRISM_OK", ...); never NULL. */
 PRISM_API const char* prism_status_string(prism_status_t s);
 

@@ -103,6 +103,8 @@ def load_library():
     lib.prism_scan_u32.restype = ctypes.c_int
     lib.prism_scan_check.argtypes = [vp, vp]
     lib.prism_scan_check.restype = ctypes.c_int
+    lib.prism_mfma_probe.argtypes = [ctypes.c_int32, vp, sz, ctypes.c_int32, vp, sz, vp]
+    lib.prism_mfma_probe.restype = ctypes.c_int
     lib.prism_scan_u32_static.argtypes = [vp, vp, i64, vp, vp]
     lib.prism_scan_u32_static.restype = ctypes.c_int
     _lib = lib
@@ -156,6 +158,16 @@ def prism_sched_map(wg, tiles_m, tiles_n, units):
     s = load_library().prism_sched_map(wg, tiles_m, tiles_n, units, ctypes.byref(tm), ctypes.byref(tn),
                                        ctypes.byref(u))
     return s, tm.value, tn.value, u.value
+
+
+MFMA_PROBE_OPERAND_BYTES = 33554432
+MFMA_PROBE_COUNTER_BYTES = 32768
+MFMA_PROBE_FLOP_PER_ITERATION = 2147483648.0
+
+
+def prism_mfma_probe(ab_dtype, operands, operand_bytes, iterations, counters, counter_bytes, hip_stream=None) -> int:
+    return load_library().prism_mfma_probe(int(ab_dtype), _p(operands), operand_bytes, iterations, _p(counters),
+                                           counter_bytes, _p(hip_stream))
 
 
 def prism_status_string(status: int) -> str:

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libprism_gemm.so")
-_UNITS = ["kernels.hip", "host_api.hip", "scan.hip"]
+_UNITS = ["kernels.hip", "host_api.hip", "scan.hip", "probe.hip"]
 _FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     # keep the compiler from forming packed fp32 vector ops out of scalar float code
