@@ -12,8 +12,8 @@ __global__ void kernel(float* out)
 {
     const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
     const persp::Wave w = wgp.wave();
-    const auto producers = wgp.split<1, 4>();      // one of four waves: an even split
-    f32x4 acc = per_wave(producers.wave(), bf16x8{}, bf16x8{}, f32x4{0, 0, 0, 0});
+    const persp::Threads<128> pair = wgp.destruct().group<128>();   // two of the four waves
+    f32x4 acc = per_wave(pair.group<64>(), bf16x8{}, bf16x8{}, f32x4{0, 0, 0, 0});
     acc = per_wave(w, bf16x8{}, bf16x8{}, acc);
     wg::barrier(wgp);                              // workgroup-collective: allowed with the workgroup token
     out[threadIdx.x] = acc[0];
