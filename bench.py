@@ -322,7 +322,7 @@ def main() -> int:
         roofline["mfma_probe_tflops"] = probe["tflops_loop"]
         roofline["mfma_probe_clock_mhz"] = probe["clock_mhz"]
         roofline["frac_of_probe"] = round(achieved / probe["tflops_loop"], 4)
-    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent", 4: "gemm_streamk"}.get(plan.kernel, "none")
+    roofline["kernel"] = {1: "gemm_staged", 2: "gemm_pipelined", 3: "gemm_persistent"}.get(plan.kernel, "none")
     roofline["launch_us"] = round(launch_ms * 1e3, 2)
     measured = MEASURED_TRAFFIC.get(w.name)
     if measured and measured[1] == source_digest():

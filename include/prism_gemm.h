@@ -14,7 +14,8 @@
  *
  * All pointers named "device" are HIP device pointers owned by the caller; the
  * library never allocates or frees memory and keeps no mutable global state
- * apart from cached device properties.  Calls enqueue work on the given HIP
+ * apart from its experiment hooks, read once from the environment (see
+ * prism_reread_environment).  It is written for one MI355X: 256 compute units in 8 dies.  Calls enqueue work on the given HIP
  * stream and return without synchronising; every buffer must stay valid until
  * the stream has executed the work.  Calls are re-entrant.  Every argument
  * error is detected on the host before anything is launched and reported as
@@ -85,9 +86,7 @@ typedef struct prism_gemm_plan {
     int32_t kernel;          /* 0 = nothing to launch, 1 = staged (any layout/alignment),
                                 2 = direct-to-LDS pipeline (aligned operands),
                                 3 = the same pipeline, persistent: used for more tiles
-                                    than compute units with short K loops,
-                                4 = its stream-K form (only with PRISM_STREAMK=1 in the
-                                    environment; needs workspace_bytes of workspace)   */
+                                    than compute units with short K loops              */
     int32_t tile_m, tile_n, tile_k; /* workgroup tile                                */
     int32_t waves;           /* wavefronts per workgroup                              */
     int32_t split_k;         /* K slices actually used (>= 1)                         */
@@ -194,11 +193,38 @@ PRISM_API prism_status_t prism_mfma_probe(int32_t ab_dtype, const void* operands
                                           int32_t iterations, uint64_t* counters, size_t counter_bytes,
                                           void* hip_stream);
 
+/*
+ * Test aid: shows, on the device, the two lane layouts the kernels are built on, through the
+ * very device functions the kernels use (one wavefront, a few microseconds).
+ *
+ * PRISM_LAYOUT_ACCUMULATOR_BF16 / _F16: in0 = R, in1 = C, each a row-major 16 x 32 matrix of
+ *   the 16-bit type; out = row-major 16 x 16 fp32 matrix that must equal R * C^T: one matrix
+ *   instruction, its accumulator registers placed by the library's lane -> (row, column) map.
+ * PRISM_LAYOUT_K_ROWS_READ: in0 = row-major 32 x 128 matrix of 16-bit values (k-rows of an
+ *   operand that is not contiguous along K), in1 unused; out = row-major 128 x 32 matrix that must
+ *   be its transpose: the transposing LDS reads of the pipeline, placed by the documented layout.
+ * Pointers are device pointers, 16-byte aligned.  Other values of `what`: PRISM_ERR_UNSUPPORTED.
+ */
+#define PRISM_LAYOUT_ACCUMULATOR_BF16 0
+#define PRISM_LAYOUT_ACCUMULATOR_F16 1
+#define PRISM_LAYOUT_K_ROWS_READ 2
+PRISM_API prism_status_t prism_layout_probe(int32_t what, const void* in0, const void* in1, void* out, void* hip_stream);
+
 /* Static string for a status code ("PRISM_OK", ...); never NULL. */
 PRISM_API const char* prism_status_string(prism_status_t s);
 
 /* Library version, major*10000 + minor*100 + patch. */
 PRISM_API int prism_version(void);
+
+/*
+ * The library reads its test and experiment hooks from the environment once, at the first call
+ * that needs them, and keeps them: PRISM_GEMM_CONFIG=0|1 (pin 256x256 / 128x128 tiles of the
+ * pipeline), PRISM_PERSISTENT=0|1 (never / whenever possible use the persistent kernel),
+ * PRISM_LOG=1 (one line per launch on stderr: problem, kernel, tile, split),
+ * PRISM_SCAN_SPIN_LIMIT=<polls> (bound of the scan's look-back wait).  This call reads them
+ * again, for a process that changes its environment after the first call (tests do).
+ */
+PRISM_API void prism_reread_environment(void);
 
 #ifdef __cplusplus
 }

@@ -105,6 +105,10 @@ def load_library():
     lib.prism_scan_check.restype = ctypes.c_int
     lib.prism_mfma_probe.argtypes = [ctypes.c_int32, vp, sz, ctypes.c_int32, vp, sz, vp]
     lib.prism_mfma_probe.restype = ctypes.c_int
+    lib.prism_reread_environment.argtypes = []
+    lib.prism_reread_environment.restype = None
+    lib.prism_layout_probe.argtypes = [ctypes.c_int32, vp, vp, vp, vp]
+    lib.prism_layout_probe.restype = ctypes.c_int
     lib.prism_scan_u32_static.argtypes = [vp, vp, i64, vp, vp]
     lib.prism_scan_u32_static.restype = ctypes.c_int
     _lib = lib
@@ -170,12 +174,23 @@ def prism_mfma_probe(ab_dtype, operands, operand_bytes, iterations, counters, co
                                            counter_bytes, _p(hip_stream))
 
 
+LAYOUT_ACCUMULATOR_BF16, LAYOUT_ACCUMULATOR_F16, LAYOUT_K_ROWS_READ = 0, 1, 2
+
+
+def prism_layout_probe(what, in0, in1, out, hip_stream=None) -> int:
+    return load_library().prism_layout_probe(int(what), _p(in0), _p(in1), _p(out), _p(hip_stream))
+
+
 def prism_status_string(status: int) -> str:
     return load_library().prism_status_string(int(status)).decode()
 
 
 def prism_version() -> int:
     return load_library().prism_version()
+
+
+def prism_reread_environment() -> None:
+    load_library().prism_reread_environment()
 
 
 # ---- convenience for torch tensors ----------------------------------------------------------

@@ -3,8 +3,10 @@
 // here; everything numeric runs in the device kernels.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/prism_gemm.h"
 #include "grid.hpp"
@@ -49,13 +51,38 @@ bool overlaps(const void* a, int64_t a_bytes, const void* b, int64_t b_bytes)
     return a0 < b0 + static_cast<uintptr_t>(b_bytes) && b0 < a0 + static_cast<uintptr_t>(a_bytes);
 }
 
-int forced_pipe_config()
+// Hooks for tests and experiments, read from the environment once (at the first call that
+// needs them, or again on prism_reread_environment) and kept:
+//   PRISM_GEMM_CONFIG=<index>  pins the pipeline's tile configuration (0: 256x256, 1: 128x128)
+//   PRISM_PERSISTENT=0|1       never / whenever possible use the persistent kernel
+//   PRISM_LOG=1                one line per launch on stderr: problem, kernel, tile, split
+struct Hooks {
+    int pipe_config = -1;  // -1: the library decides
+    int persistent = -1;   // -1: the library decides, 0: never, 1: whenever possible
+    bool log = false;
+};
+Hooks g_hooks;
+bool g_hooks_loaded = false;
+std::mutex g_hooks_mutex;
+
+void load_hooks_locked()
 {
-    // Experiment hook: PRISM_GEMM_CONFIG=<index> pins the pipeline tile configuration.
-    const char* e = std::getenv("PRISM_GEMM_CONFIG");
-    if (!e || !*e) return -1;
-    const int v = std::atoi(e);
-    return v >= 0 && v < prism::kNumPipeConfigs ? v : -1;
+    Hooks h;
+    if (const char* e = std::getenv("PRISM_GEMM_CONFIG"); e && *e) {
+        const int v = std::atoi(e);
+        if (v >= 0 && v < prism::kNumPipeConfigs) h.pipe_config = v;
+    }
+    if (const char* e = std::getenv("PRISM_PERSISTENT"); e && (e[0] == '0' || e[0] == '1')) h.persistent = e[0] - '0';
+    if (const char* e = std::getenv("PRISM_LOG"); e && e[0] == '1') h.log = true;
+    g_hooks = h;
+    g_hooks_loaded = true;
+}
+
+Hooks hooks()
+{
+    std::lock_guard<std::mutex> lock(g_hooks_mutex);
+    if (!g_hooks_loaded) load_hooks_locked();
+    return g_hooks;
 }
 
 // Validates everything, normalises to a row-major C and chooses the launch.
@@ -79,6 +106,7 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     if (!(d->alpha == d->alpha) || !(d->beta == d->beta)) return PRISM_ERR_INVALID_ARG;  // NaN scales
 
     std::memset(out, 0, sizeof(*out));
+    const Hooks hk = hooks();
     prism_gemm_plan_t& plan = out->plan;
     plan.split_k = 1;
     const bool empty = M == 0 || N == 0 || batch == 0;
@@ -166,7 +194,7 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     plan.kernel = 1;
     if (pipe_ok) {
         plan.kernel = 2;
-        int cfg = forced_pipe_config();
+        int cfg = hk.pipe_config;
         if (cfg > 1) cfg = -1;  // the hook names a tile size (0: 256x256, 1: 128x128)
         if (cfg < 0) {
             // Big tiles when they give at least half of the compute units a workgroup, or for a
@@ -240,8 +268,7 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
     // the hardware's own dealing of workgroups to free compute units balances better than the
     // fixed assignment of the persistent kernel (measured).
     {
-        const char* e = std::getenv("PRISM_PERSISTENT");  // experiment hook: 0 = never, 1 = whenever possible
-        const bool never = e && e[0] == '0', always = e && e[0] == '1';
+        const bool never = hk.persistent == 0, always = hk.persistent == 1;
         const int64_t last_slice_steps = ksteps - (split - 1) * slice_steps;
         const bool possible = plan.kernel == 2 && out->pipe_config == 0 && slice_steps >= 2 && last_slice_steps >= 2 &&
                               slice_steps % 2 == 0 && last_slice_steps % 2 == 0;  // it walks K two steps at a time
@@ -250,31 +277,6 @@ prism_status_t make_problem(const prism_gemm_desc_t* d, int64_t M, int64_t N, in
             plan.kernel = 3;
             out->total_units = static_cast<int>(units * split);
             if (plan.workgroups > kComputeUnits) plan.workgroups = kComputeUnits;
-        }
-    }
-    // Stream-K (opt-in, PRISM_STREAMK=1): the K steps of all 256x256 tiles are dealt evenly to 256
-    // workgroups, which exchange partial tiles through the workspace.  It evens out a badly
-    // filled last round of compute units (5120^3: 400 tiles, a round of 256 and one of 144), but
-    // the workgroups of a die then no longer walk K in step and stop sharing operand panels in
-    // the L2: measured 269 against 190 us on 5120^3 and 416 against 343 us on 6144^3, so the
-    // library never chooses it by itself.  One problem, no K split, an even number of K steps;
-    // without the workspace it falls back to one workgroup per tile.
-    {
-        const char* e = std::getenv("PRISM_STREAMK");
-        const bool wanted = e && e[0] == '1';
-        const bool possible = (plan.kernel == 2 || plan.kernel == 3) && out->pipe_config == 0 && batch == 1 && split == 1 &&
-                              d->split_k == 0 && ksteps % 2 == 0 && ksteps >= 2 && units >= kComputeUnits;
-        const bool have_ws = !need_pointers || (d->workspace && d->workspace_bytes >= prism::kStreamKWorkspaceBytes &&
-                                                aligned(d->workspace, 16));
-        if (possible && wanted) {
-            ws_need = prism::kStreamKWorkspaceBytes;
-            if (have_ws) {
-                plan.kernel = 4;
-                plan.workgroups = prism::kStreamKWorkgroups;
-                p.partial = static_cast<float*>(d->workspace);
-            } else {
-                ws_need = 0;
-            }
         }
     }
     plan.workspace_bytes = ws_need;
@@ -287,15 +289,20 @@ prism_status_t run(const Problem& pr, hipStream_t stream)
     const GemmParams& p = pr.p;
     if (p.M == 0 || p.N == 0 || p.batch == 0) return PRISM_OK;
     hipError_t e = hipSuccess;
-    if (pr.plan.kernel == 4)
-        e = prism::launch_streamk(pr.ab_dtype, p, stream);
-    else if (pr.plan.kernel == 3)
+    if (pr.plan.kernel == 3)
         e = prism::launch_persistent(pr.ab_dtype, p, pr.total_units, static_cast<int>(pr.plan.workgroups), stream);
     else if (pr.plan.kernel == 2)
         e = prism::launch_pipelined(pr.pipe_config, pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);
     else if (pr.plan.kernel == 1)
         e = prism::launch_staged(pr.ab_dtype, p, static_cast<int>(pr.plan.workgroups), stream);
     if (e != hipSuccess) return PRISM_ERR_LAUNCH;
+    if (hooks().log) {
+        static const char* const names[] = {"none", "gemm_staged", "gemm_pipelined", "gemm_persistent"};
+        std::fprintf(stderr, "prism_gemm: M=%d N=%d K=%d batch=%d%s kernel=%s tile=%dx%dx%d waves=%d split_k=%d workgroups=%lld\n",
+                     p.M, p.N, p.K, p.batch, pr.plan.swapped ? " (run as C^T = B^T A^T)" : "",
+                     names[pr.plan.kernel >= 0 && pr.plan.kernel <= 3 ? pr.plan.kernel : 0], pr.plan.tile_m, pr.plan.tile_n,
+                     pr.plan.tile_k, pr.plan.waves, pr.plan.split_k, static_cast<long long>(pr.plan.workgroups));
+    }
     if (p.split_k != 1) {  // K == 0 (split_k == 0) or a real split: the reduction writes C
         e = prism::launch_reduce(p, stream);
         if (e != hipSuccess) return PRISM_ERR_LAUNCH;
@@ -382,6 +389,15 @@ const char* prism_status_string(prism_status_t s)
     return "PRISM_ERR_UNKNOWN";
 }
 
-int prism_version(void) { return 100; }
+int prism_version(void) { return 200; }
+
+void prism_reread_environment(void)
+{
+    {
+        std::lock_guard<std::mutex> lock(g_hooks_mutex);
+        load_hooks_locked();
+    }
+    prism::scan_reread_environment();
+}
 
 }  // extern "C"

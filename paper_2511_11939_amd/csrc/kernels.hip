@@ -49,17 +49,9 @@ __device__ __forceinline__ Placement place(const GemmParams& p, int wg)
 // OWN_PATCH false: the patches reuse the operand slots; workgroup-collective, every wave
 // must call it (it starts with a barrier that retires the slots).  OWN_PATCH true: `patch`
 // is this wave's private 16-row patch outside the slots; no barrier, 16 rows per pass.
-// Partial sums of the same workgroup tile computed elsewhere (stream-K): `count` row-major
-// 256 x 256 fp32 tiles, kPartialTile floats apart, added to the accumulators on their way out.
-constexpr int kPartialSide = 256, kPartialTile = kPartialSide * kPartialSide;
-struct Addends {
-    const float* first = nullptr;
-    int count = 0;
-};
-
-template <typename TileT, int MT, int NT, bool OWN_PATCH = false, bool PAIRED = false, bool ADD = false>
+template <typename TileT, int MT, int NT, bool OWN_PATCH = false, bool PAIRED = false>
 __device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams& p, const Placement& q, const TileT& acc,
-                                         int m_wave, int n_wave, char* lds, int wave, int lane, Addends add = Addends{})
+                                         int m_wave, int n_wave, char* lds, int wave, int lane)
 {
     const persp::Wave wv = wgp.wave();
     const int esize = p.c_dtype == DT_F32 ? 4 : 2;
@@ -86,7 +78,6 @@ __device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams&
             constexpr int RUNS = NT / 2;
             const int n_lane = n_wave + 8 * (lane >> 4);
             const int64_t row_bytes = p.ldc * esize;
-            const float* add_lane = add.first + (m_wave - q.m0 + (lane & 15)) * kPartialSide + (n_lane - q.n0);
             auto run = [&](auto out_c, auto bias_c) {
                 constexpr int OUT = decltype(out_c)::value;
                 constexpr bool BIAS = decltype(bias_c)::value;
@@ -100,19 +91,9 @@ __device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams&
                         bias[s][4] = b1[0]; bias[s][5] = b1[1]; bias[s][6] = b1[2]; bias[s][7] = b1[3];
                     }
                 }
-                auto addends = [&](int r_uniform, int c_uniform, f32x4& lo, f32x4& hi) {
-                    if constexpr (ADD) {
-                        const float* a = add_lane + r_uniform * kPartialSide + c_uniform;
-                        for (int k = 0; k < add.count; ++k, a += kPartialTile) {
-                            lo += *reinterpret_cast<const f32x4*>(a);
-                            hi += *reinterpret_cast<const f32x4*>(a + 4);
-                        }
-                    }
-                };
                 if constexpr (OUT == DT_F32) {
                     char* lane_base = c_problem + (m_wave + (lane & 15)) * row_bytes + static_cast<int64_t>(n_lane) * 4;
                     wg::drain_pairs<MT, NT>(wv, acc, [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
-                        addends(r_uniform, c_uniform, lo, hi);
                         grid::finish_run<OUT, BIAS>(lane_base + r_uniform * row_bytes + c_uniform * 4, p.alpha, bias[BIAS ? c_uniform / 32 : 0], lo, hi);
                     });
                 } else {
@@ -120,8 +101,7 @@ __device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams&
                     wg::drain_rows<MT, NT>(
                         wv, acc, patch, lane,
                         [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
-                            addends(r_uniform, c_uniform, lo, hi);
-                            return grid::pack_run<OUT, BIAS>(p.alpha, bias[BIAS ? c_uniform / 32 : 0], lo, hi);
+                                return grid::pack_run<OUT, BIAS>(p.alpha, bias[BIAS ? c_uniform / 32 : 0], lo, hi);
                         },
                         [&](int r_uniform, int r_lane, int byte_in_row, u32x4 piece) {
                             __builtin_nontemporal_store(piece, reinterpret_cast<u32x4*>(wave_base + (r_uniform + r_lane) * row_bytes + byte_in_row));
@@ -184,26 +164,7 @@ __device__ __forceinline__ void epilogue(persp::Workgroup wgp, const GemmParams&
             return;
         }
     }
-    drain_any([&](int r, int c, f32x4 v) {
-        if constexpr (ADD) {
-            const float* a = add.first + (m_wave - q.m0 + r) * kPartialSide + (n_wave - q.n0 + c);
-            for (int k = 0; k < add.count; ++k, a += kPartialTile) v += *reinterpret_cast<const f32x4*>(a);
-        }
-        grid::finish4_any(p, c_problem, m_wave + r, n_wave + c, v);
-    });
-}
-
-// One wave's accumulators (paired block columns) into a row-major 256 x 256 fp32 tile (`slot`),
-// as runs of eight consecutive n straight from the registers.  row0 / col0: the wave tile's place.
-template <typename TileT, int MT, int NT>
-__device__ __forceinline__ void store_partial_tile(persp::Wave wv, const TileT& acc, int lane, float* slot, int row0, int col0)
-{
-    float* base = slot + (row0 + (lane & 15)) * kPartialSide + col0 + 8 * (lane >> 4);
-    wg::drain_pairs<MT, NT>(wv, acc, [&](int r_uniform, int c_uniform, f32x4 lo, f32x4 hi) {
-        float* dst = base + r_uniform * kPartialSide + c_uniform;
-        *reinterpret_cast<f32x4*>(dst) = lo;
-        *reinterpret_cast<f32x4*>(dst + 4) = hi;
-    });
+    drain_any([&](int r, int c, f32x4 v) { grid::finish4_any(p, c_problem, m_wave + r, n_wave + c, v); });
 }
 
 template <typename P, int BM, int BN, int BK, int WAVES_N>
@@ -282,135 +243,6 @@ __global__ __launch_bounds__(256) void gemm_persistent(const GemmParams p, const
         [&]() {
             cur = nxt;
             tile += gridDim.x;
-        });
-}
-
-// Stream-K form of the persistent kernel, for tile counts that fill the last round of compute
-// units badly.  The K steps of all tiles form one sequence per die (the die's run of tiles in
-// the locality order, tile after tile); the 32 workgroups of a die take equal, contiguous
-// pieces of it in the order of a per-die ticket, so a workgroup computes the end of one tile,
-// some whole tiles and the beginning of another.  A workgroup that does not reach the end of a
-// tile writes its fp32 accumulators to its slot of the workspace and raises its flag; the one
-// that reaches the end adds the slots of the tickets before it that worked on the tile, in
-// ticket order (so the sum is the same in every run), and does the epilogue.  It only waits
-// for lower tickets of its own die, and those workgroups are already running; as every piece
-// is walked from its end, they wrote their slot at the very start.  The wait is
-// bounded; a give-up sets the error word of the workspace.  p.partial is the workspace.
-__global__ __launch_bounds__(256) void streamk_init(uint32_t* header)
-{
-    for (int i = threadIdx.x; i < kStreamKHeaderBytes / 4; i += blockDim.x) header[i] = 0u;
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void gemm_streamk(const GemmParams p)
-{
-    const persp::Workgroup wgp = persp::Grid::at_kernel_entry().workgroup();
-    using P = wg::PersistentPipe<T>;
-    __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
-    uint32_t* s_ticket = reinterpret_cast<uint32_t*>(lds + P::PATCH_BASE);  // the LDS is full: borrowed before the first epilogue
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    char* ws = reinterpret_cast<char*>(p.partial);
-    uint32_t* header = reinterpret_cast<uint32_t*>(ws);
-    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + kStreamKFlagsOffset);
-    const int die = blockIdx.x % grid::kDies, per_die = gridDim.x / grid::kDies;
-
-    if (threadIdx.x == 0) *s_ticket = __hip_atomic_fetch_add(header + die, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    wg::sync(wgp);
-    const int ticket = __builtin_amdgcn_readfirstlane(*s_ticket);  // 0 .. per_die-1 within the die
-    wg::sync(wgp);                                                 // everyone has read it before the patch is used
-    const int slot = die * per_die + ticket;
-    float* my_slot = reinterpret_cast<float*>(ws + kStreamKHeaderBytes + slot * kStreamKSlotBytes);
-
-    const int ksteps = p.K / P::BK;                                // even, the host guarantees it
-    int first_tile, n_tiles;
-    grid::die_run(die, p.tiles_m * p.tiles_n, first_tile, n_tiles);
-    const int steps = n_tiles * ksteps;
-    int piece = (steps + per_die - 1) / per_die;
-    piece += piece & 1;                                            // pieces of an even number of K steps
-    const int begin = ticket * piece, end = begin + piece < steps ? begin + piece : steps;
-    if (begin >= end) return;                                      // uniform: the whole workgroup leaves
-
-    struct Segment {
-        int tile, k0, k1, m0, n0;                                  // K steps [k0, k1) of tile `tile` of the die's run
-    };
-    // the piece is walked from its end to its beginning (K ascending inside a segment): the part
-    // of a tile that a lower ticket owns is then computed first thing, and is long there when
-    // the ticket that ends the tile, last thing, comes to fetch it
-    auto segment_ending_at = [&](int stop) {
-        Segment g;
-        g.tile = (stop - 1) / ksteps;
-        g.k1 = stop - g.tile * ksteps;
-        g.k0 = g.k1 - (stop - begin) > 0 ? g.k1 - (stop - begin) : 0;
-        int tm, tn;
-        grid::tile_at(first_tile + g.tile, p.tiles_m, p.tiles_n, tm, tn);
-        g.m0 = tm * P::BM;
-        g.n0 = tn * P::BN;
-        return g;
-    };
-    auto source = [&](const Segment& g) {
-        typename P::Source s;
-        s.a = p.A + 2 * (g.m0 * p.a_sm + static_cast<int64_t>(g.k0) * P::BK);
-        s.b = p.B + 2 * (g.n0 * p.b_sn + static_cast<int64_t>(g.k0) * P::BK);
-        s.a_ld = static_cast<uint32_t>(2 * p.a_sm);
-        s.b_ld = static_cast<uint32_t>(2 * p.b_sn);
-        s.a_rows = p.M - g.m0 < P::BM ? p.M - g.m0 : P::BM;
-        s.b_rows = p.N - g.n0 < P::BN ? p.N - g.n0 : P::BN;
-        return s;
-    };
-
-    int stop = end;  // the part of the piece not yet computed is [begin, stop)
-    Segment cur = segment_ending_at(stop), nxt = cur;
-    P::run(
-        wgp, lds, wave, lane, source(cur), cur.k1 - cur.k0,
-        [&](typename P::Source& s, int& n) {
-            const int next_stop = stop - (cur.k1 - cur.k0);
-            if (next_stop <= begin) return false;
-            nxt = segment_ending_at(next_stop);
-            s = source(nxt);
-            n = nxt.k1 - nxt.k0;
-            return true;
-        },
-        [&](typename P::tile_t& acc) {
-            int lane_now = lane;
-            asm volatile("" : "+v"(lane_now));
-            char* patch = lds + P::PATCH_BASE + wave * P::PATCH_BYTES;
-            const int row0 = (wave / P::WAVES_N) * P::WTM, col0 = (wave % P::WAVES_N) * P::WTN;
-            if (cur.k1 < ksteps) {
-                // the tile is finished by a higher ticket: hand the partial sums over
-                store_partial_tile<typename P::tile_t, P::MT, P::NT>(wgp.wave(), acc, lane_now, my_slot, row0, col0);
-                __threadfence();
-                wg::sync(wgp);
-                if (threadIdx.x == 0) __hip_atomic_store(flags + slot, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                return;
-            }
-            Addends add;
-            if (cur.k0 > 0) {
-                // the tile was begun by lower tickets: the one whose piece holds its first step,
-                // and every ticket between that one and this
-                const int first_ticket = (cur.tile * ksteps) / piece;
-                for (int t = first_ticket; t < ticket; ++t) {
-                    uint32_t polls = 0;
-                    while (__hip_atomic_load(flags + die * per_die + t, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-                        if (++polls > (1u << 22)) {
-                            __hip_atomic_store(header + kStreamKErrorOffset / 4, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(2);
-                    }
-                }
-                add.first = reinterpret_cast<const float*>(ws + kStreamKHeaderBytes + (die * per_die + first_ticket) * kStreamKSlotBytes);
-                add.count = ticket - first_ticket;
-            }
-            Placement q;
-            q.batch = 0; q.slice = 0; q.m0 = cur.m0; q.n0 = cur.n0; q.k_begin = 0; q.k_end = p.K;
-            epilogue<typename P::tile_t, P::MT, P::NT, true, P::PAIRED_N, true>(wgp, p, q, acc, cur.m0 + (wave / P::WAVES_N) * P::WTM,
-                                                                                cur.n0 + (wave % P::WAVES_N) * P::WTN,
-                                                                                patch, wave, lane_now, add);
-        },
-        [&]() {
-            stop -= cur.k1 - cur.k0;
-            cur = nxt;
         });
 }
 
@@ -504,16 +336,6 @@ hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int w
     }
     return ab_dtype == DT_BF16 ? launch_pipe_config<bf16_t>(config, p, workgroups, stream)
                                : launch_pipe_config<f16_t>(config, p, workgroups, stream);
-}
-
-hipError_t launch_streamk(int ab_dtype, const GemmParams& p, hipStream_t stream)
-{
-    hipLaunchKernelGGL(streamk_init, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(p.partial));
-    if (ab_dtype == DT_BF16)
-        hipLaunchKernelGGL(gemm_streamk<bf16_t>, dim3(kStreamKWorkgroups), dim3(256), 0, stream, p);
-    else
-        hipLaunchKernelGGL(gemm_streamk<f16_t>, dim3(kStreamKWorkgroups), dim3(256), 0, stream, p);
-    return hipGetLastError();
 }
 
 hipError_t launch_persistent(int ab_dtype, const GemmParams& p, int total, int workgroups, hipStream_t stream)

@@ -18,22 +18,18 @@ extern const PipeConfig kPipeConfigs[kNumPipeConfigs];
 
 constexpr int kStagedTileM = 128, kStagedTileN = 128, kStagedWaves = 4;
 
-// Stream-K form of the 256x256 pipeline: workspace = header (per-die ticket counters, error
-// word, one flag per workgroup) followed by one fp32 partial tile per workgroup.
-constexpr int kStreamKWorkgroups = 256, kStreamKHeaderBytes = 4096, kStreamKFlagsOffset = 64, kStreamKErrorOffset = 32;
-constexpr size_t kStreamKSlotBytes = 256 * 256 * 4;
-constexpr size_t kStreamKWorkspaceBytes = kStreamKHeaderBytes + kStreamKWorkgroups * kStreamKSlotBytes;
-
 // Each returns the launch error of the HIP runtime (hipSuccess when accepted).
 // `workgroups` = p.tiles_m * p.tiles_n * p.batch * p.split_k.
 hipError_t launch_pipelined(int config, int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream);
 hipError_t launch_staged(int ab_dtype, const GemmParams& p, int workgroups, hipStream_t stream);
 // 256x256x64 tile, `workgroups` persistent workgroups walking `total` (tile, unit) pairs;
 // every unit must span at least two K steps of 64.
-hipError_t launch_streamk(int ab_dtype, const GemmParams& p, hipStream_t stream);
 hipError_t launch_persistent(int ab_dtype, const GemmParams& p, int total, int workgroups, hipStream_t stream);
 // Sums the split_k partial slabs in slice order and applies the epilogue; with
 // p.split_k == 0 it writes C <- bias + beta*C (the K == 0 case).
 hipError_t launch_reduce(const GemmParams& p, hipStream_t stream);
+
+// The scan's own hook (PRISM_SCAN_SPIN_LIMIT), read again from the environment.
+void scan_reread_environment();
 
 }  // namespace prism

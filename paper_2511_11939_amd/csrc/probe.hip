@@ -72,8 +72,81 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_probe(const u32x4* __restr
     }
 }
 
+// ---- layout probes: the lane layouts the kernels rely on, shown on the device ------------------
+// One wavefront each.  They use the very functions the GEMM kernels use, so a wrong layout
+// assumption in those functions shows up as a wrong matrix on the host.
+
+// D = R * C^T for a 16 x 32 row operand R and a 16 x 32 column operand C (both row-major, K
+// contiguous), one matrix instruction; the accumulators are scattered to a row-major 16 x 16
+// matrix with lane::acc_row / lane::acc_col.
+template <typename T>
+__global__ __launch_bounds__(64) void probe_accumulator_layout(const char* r_bits, const char* c_bits, float* d_out)
+{
+    const persp::Wave wv = persp::Grid::at_kernel_entry().workgroup<64>().wave();
+    using frag_t = typename Frag<T>::type;
+    const int lane = threadIdx.x;
+    // the fragment a lane holds: 8 consecutive k of row lane % 16, k-quarter lane / 16 (lane::load_fragment)
+    const int row = lane & 15, k0 = 8 * (lane >> 4);
+    const frag_t r = __builtin_bit_cast(frag_t, *reinterpret_cast<const u32x4*>(r_bits + (row * 32 + k0) * 2));
+    const frag_t c = __builtin_bit_cast(frag_t, *reinterpret_cast<const u32x4*>(c_bits + (row * 32 + k0) * 2));
+    const f32x4 acc = wave::mfma_block(wv, r, c, f32x4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) d_out[lane::acc_row(reg, lane) * 16 + lane::acc_col(lane)] = acc[reg];
+}
+
+// A 32 (k) x 128 (elements) 16-bit matrix, row-major, is laid into LDS as the pipeline lays an
+// operand kept as k-rows; every fragment half is fetched with wave::read_k_rows_half and written
+// out as out[element][k] -- the transposed matrix if the documented lane layout holds.
+__global__ __launch_bounds__(64) void probe_k_rows_read(const uint16_t* in, uint16_t* out)
+{
+    const persp::Wave wv = persp::Grid::at_kernel_entry().workgroup<64>().wave();
+    constexpr int ROW_BYTES = 256;
+    __shared__ __attribute__((aligned(1024))) char tile[32 * ROW_BYTES];
+    const int lane = threadIdx.x;
+    for (int q = lane; q < 32 * 16; q += 64) {  // 16-byte chunk c of k-row k at chunk position c ^ 2*(k % 4)
+        const int k = q / 16, c = q % 16;
+        *reinterpret_cast<u32x4*>(tile + k * ROW_BYTES + ((c ^ (2 * (k % 4))) * 16)) =
+            *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(in) + k * ROW_BYTES + c * 16);
+    }
+    __syncthreads();
+    uint32_t part[4];
+#pragma unroll
+    for (int jl = 0; jl < 4; ++jl) part[jl] = wave::k_rows_lane_part<ROW_BYTES>(wv, jl, lane);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const wave::v4s v = wave::read_k_rows_half<ROW_BYTES>(wv, tile, 0, j, 0, h, part);
+            // lane (g = lane / 16, i = lane % 16): element 16 j + i, k = 8 g + 4 h + 0..3
+            const int element = 16 * j + (lane & 15), k = 8 * (lane >> 4) + 4 * h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[element * 32 + k + e] = static_cast<uint16_t>(v[e]);
+        }
+}
+
 }  // namespace
 }  // namespace prism
+
+extern "C" prism_status_t prism_layout_probe(int32_t what, const void* in0, const void* in1, void* out, void* hip_stream)
+{
+    using namespace prism;
+    if (!in0 || !out || reinterpret_cast<uintptr_t>(in0) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0) return PRISM_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (what == PRISM_LAYOUT_ACCUMULATOR_BF16 || what == PRISM_LAYOUT_ACCUMULATOR_F16) {
+        if (!in1 || reinterpret_cast<uintptr_t>(in1) % 16 != 0) return PRISM_ERR_INVALID_ARG;
+        const char* r = static_cast<const char*>(in0);
+        const char* c = static_cast<const char*>(in1);
+        if (what == PRISM_LAYOUT_ACCUMULATOR_BF16)
+            hipLaunchKernelGGL(probe_accumulator_layout<bf16_t>, dim3(1), dim3(64), 0, stream, r, c, static_cast<float*>(out));
+        else
+            hipLaunchKernelGGL(probe_accumulator_layout<f16_t>, dim3(1), dim3(64), 0, stream, r, c, static_cast<float*>(out));
+    } else if (what == PRISM_LAYOUT_K_ROWS_READ) {
+        hipLaunchKernelGGL(probe_k_rows_read, dim3(1), dim3(64), 0, stream, static_cast<const uint16_t*>(in0), static_cast<uint16_t*>(out));
+    } else {
+        return PRISM_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_ERR_LAUNCH;
+}
 
 extern "C" prism_status_t prism_mfma_probe(int32_t ab_dtype, const void* operands, size_t operand_bytes, int32_t iterations,
                                            uint64_t* counters, size_t counter_bytes, void* hip_stream)

@@ -17,6 +17,7 @@
 #include <mutex>
 
 #include "../../include/prism_scan.h"
+#include "launch.hpp"
 #include "persp.hpp"
 
 namespace prism {
@@ -211,13 +212,27 @@ namespace {
 
 bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Test hook: PRISM_SCAN_SPIN_LIMIT=<polls> shortens the bounded wait of the look-back.  Read
+// once and kept; prism_reread_environment reads it again.
+std::mutex g_spin_mutex;
+bool g_spin_loaded = false;
+uint32_t g_spin_limit = prism::scan::kDefaultSpinLimit;
+
+void load_spin_limit_locked()
+{
+    g_spin_limit = prism::scan::kDefaultSpinLimit;
+    if (const char* e = std::getenv("PRISM_SCAN_SPIN_LIMIT"); e && *e) {
+        const long v = std::atol(e);
+        g_spin_limit = v < 0 ? 0u : static_cast<uint32_t>(v);
+    }
+    g_spin_loaded = true;
+}
+
 uint32_t spin_limit()
 {
-    // Test hook: PRISM_SCAN_SPIN_LIMIT=<polls> shortens the bounded wait of the look-back.
-    const char* e = std::getenv("PRISM_SCAN_SPIN_LIMIT");
-    if (!e || !*e) return prism::scan::kDefaultSpinLimit;
-    const long v = std::atol(e);
-    return v < 0 ? 0u : static_cast<uint32_t>(v);
+    std::lock_guard<std::mutex> lock(g_spin_mutex);
+    if (!g_spin_loaded) load_spin_limit_locked();
+    return g_spin_limit;
 }
 
 // in / out of a non-empty scan: present, 4-byte aligned, the same array or disjoint ones.
@@ -286,6 +301,14 @@ void* static_scratch_of_current_device()
 }
 
 }  // namespace
+
+namespace prism {
+void scan_reread_environment()
+{
+    std::lock_guard<std::mutex> lock(g_spin_mutex);
+    load_spin_limit_locked();
+}
+}  // namespace prism
 
 extern "C" {
 

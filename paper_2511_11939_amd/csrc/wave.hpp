@@ -50,6 +50,36 @@ __device__ __forceinline__ f32x4 mfma_part(persp::Wave, f32x4 r, f32x4 c, int e,
     return __builtin_amdgcn_mfma_f32_16x16x4f32(r[e], c[e], acc, 0, 0, 0);
 }
 
+// ---- fragments of a 16-bit operand that lies in LDS as k-rows ----------------------------
+// An operand that is contiguous along its other index (a row-major B, a column-major A) is
+// kept in LDS as k-rows of ROW_BYTES bytes: k-row k holds the elements of all n (or m) for that
+// k, its 16-byte chunk c at chunk position c ^ 2*(k % 4).  The matrix instruction wants, per
+// lane, consecutive k of ONE element; the transposing LDS read of gfx950 delivers that: the 16
+// lanes of a group each supply the address of 4 consecutive 16-bit elements, and lane i of the
+// group receives element i % 4 of the four suppliers i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With
+// supplier i pointing at k-row i/4, element quad i%4 of a block of 16 elements, lane i receives
+// four consecutive k of element i of the block.  A fragment (8 consecutive k) is two such reads.
+//
+// k_rows_lane_part: the per-lane share of the read address for the jl-th (0..3) block of 16
+// elements inside a group of 64 elements (the swizzle stays inside 8 chunks, so four values
+// serve all reads of a wave).  Lane group g = lane/16 reads k-rows 8g .. 8g+3 (+4 for the other half).
+using v4s = __attribute__((ext_vector_type(4))) short;
+template <int ROW_BYTES>
+__device__ __forceinline__ uint32_t k_rows_lane_part(persp::Wave, int jl, int lane)
+{
+    const int i = lane & 15, kq = lane >> 4, s_row = i >> 2, x = (i & 3) >> 1;
+    return (8 * kq + s_row) * ROW_BYTES + (((2 * jl + x) ^ (s_row << 1)) * lane::kChunkBytes) + (i & 1) * 8;
+}
+// Half h (k = 8*(lane/16) + 4h .. +3 of sub-step ksub) of the fragment of the j-th block of 16
+// elements counted from element `first` (a multiple of 64) of the k-rows at `tile`.
+template <int ROW_BYTES>
+__device__ __forceinline__ v4s read_k_rows_half(persp::Wave, const char* tile, int first, int j, int ksub, int h,
+                                                const uint32_t (&lane_part)[4])
+{
+    const char* src = tile + ((first >> 3) + 8 * (j / 4)) * lane::kChunkBytes + (32 * ksub + 4 * h) * ROW_BYTES + lane_part[j % 4];
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)src);
+}
+
 // Register-blocked wave tile: MT x NT accumulator blocks of 16 x 16.  The B
 // fragment is the MFMA's row operand, so every lane ends up holding runs of
 // four consecutive n for one m, which is what a row-major store wants.

@@ -56,6 +56,16 @@ __device__ __forceinline__ void barrier(persp::Workgroup) { __builtin_amdgcn_s_b
 // Barrier that also waits for the caller's outstanding LDS and memory operations.
 __device__ __forceinline__ void sync(persp::Workgroup) { __syncthreads(); }
 
+// Race check by construction: built with PRISM_PARANOID_BARRIERS, every phase of a main loop
+// that touches LDS ends with a full workgroup barrier (all of the wave's memory operations
+// waited for first).  The hand-placed waits and the one barrier per K step are meant to be
+// sufficient, so the results of that build must be bit-identical to the normal one's.
+#ifdef PRISM_PARANOID_BARRIERS
+#define PRISM_PARANOID_SYNC(wgp) ::prism::wg::sync(wgp)
+#else
+#define PRISM_PARANOID_SYNC(wgp) do { } while (0)
+#endif
+
 // One wave-wide copy of 64 x 16 bytes from global memory straight into LDS: lane l's bytes
 // land at lds_base + lds_offset + 16*l.  Wave-level: base and LDS address are per-wave
 // values; lds_offset must be a compile-time constant at the point of use, so that a copy
@@ -333,24 +343,13 @@ struct Pipeline {
             if (c < A_COPIES) copy_async_16(wv, a_tile + a_bytes, g_off[c], slot, c * NW * 1024);
             else copy_async_16(wv, b_tile + b_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
         };
-        // Half h (4 consecutive k) of the fragment whose 16 rows start at element `first` (a
-        // multiple of 16, the wave's first one a multiple of 64) of the k-rows of the tile at
-        // `tile`.  The 16 lanes of a group point at 4 k-rows x 16 elements (lane i: k-row i/4,
-        // quad i%4); the transposing read hands lane i the four k of element first + i.  The
-        // address is a constant (block of 64 elements, sub-step, half) plus a per-lane part
-        // that depends only on which 16 of the 64 elements are read (the swizzle stays inside
-        // a group of 8 chunks), so four registers serve all reads.
+        // 16-bit operands kept as k-rows: fragments come from the transposing LDS read, see
+        // wave::read_k_rows_half; four per-lane address parts serve all reads.
         uint32_t k_rows_part[4];
-        {
-            const int i = lane & 15, kq = lane >> 4, s_row = i >> 2, x = (i & 3) >> 1;
 #pragma unroll
-            for (int jl = 0; jl < 4; ++jl)
-                k_rows_part[jl] = (8 * kq + s_row) * KN_ROW_BYTES + (((2 * jl + x) ^ (s_row << 1)) * lane::kChunkBytes) + (i & 1) * 8;
-        }
+        for (int jl = 0; jl < 4; ++jl) k_rows_part[jl] = wave::k_rows_lane_part<KN_ROW_BYTES>(wv, jl, lane);
         auto read_k_rows = [&](const char* tile, int row0, int j, int ksub, int h) __attribute__((always_inline)) {
-            using v4s = __attribute__((ext_vector_type(4))) short;
-            const char* src = tile + ((row0 >> 3) + 8 * (j / 4)) * lane::kChunkBytes + (32 * ksub + 4 * h) * KN_ROW_BYTES + k_rows_part[j % 4];
-            return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)src);
+            return wave::read_k_rows_half<KN_ROW_BYTES>(wv, tile, row0, j, ksub, h, k_rows_part);
         };
         // fp32 fragment from k-rows: element e of lane (x, g) is the value at k-row 16*ksub + 4g + e,
         // element first + x; nothing to transpose, four 4-byte reads.
@@ -365,7 +364,7 @@ struct Pipeline {
 
         const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
-        using v4s = __attribute__((ext_vector_type(4))) short;
+        using v4s = wave::v4s;
         static_assert(WTM % 8 == 0 && WTN % 8 == 0 && lane::kBlock % 8 == 0, "row blocks start at multiples of 8 rows");
         uint32_t frag_part[KSUB];  // the lane's share of a fragment address, one per sub-step
 #pragma unroll
@@ -418,6 +417,7 @@ struct Pipeline {
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
+        PRISM_PARANOID_SYNC(wgp);
 
         // MFMA slots of the memory instructions of a group: reads on the even slots, copies on
         // the odd ones, so no MFMA has more than one of them in its 16-cycle shadow.
@@ -477,6 +477,7 @@ struct Pipeline {
 #pragma unroll
                     for (int m = 0; m < NM; ++m) mfma(m, cur);
                 }
+                PRISM_PARANOID_SYNC(wgp);
             }
         };
         static_assert(KSUB % 2 == 0, "fragment buffers must return to slot 0 at the end of a K step");
@@ -660,6 +661,7 @@ struct PersistentPipe {
                 mfma(m, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            PRISM_PARANOID_SYNC(wgp);
             if (switch_now) set_offsets(to);
             wait_counts<0, 0>();
             barrier(wgp);
@@ -673,6 +675,7 @@ struct PersistentPipe {
                 mfma(m, 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            PRISM_PARANOID_SYNC(wgp);
         };
         constexpr int STEP = L::kRowBytes;  // bytes one K step advances in a row
         // Keeps every accumulator block in the accumulation registers at the edges of the K

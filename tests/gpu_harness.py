@@ -81,6 +81,19 @@ def assert_matches_oracle(w: GemmWorkload, inputs: dict, c_stored: np.ndarray, *
     return res
 
 
+def assert_every_entry_matches_oracle(w: GemmWorkload, inputs: dict, c_stored: np.ndarray, *, c_dtype=None,
+                                      batch_index=0, block=2048, what=""):
+    """All rows of one problem against the oracle, a block of rows at a time (the oracle's fp64
+    outputs of a whole 16384 x 4096 result would take a gigabyte)."""
+    worst = 0.0
+    for r0 in range(0, w.M, block):
+        rows = np.arange(r0, min(r0 + block, w.M))
+        res = assert_matches_oracle(w, inputs, c_stored, c_dtype=c_dtype, rows=rows, batch_index=batch_index,
+                                    what=f"{what} rows {r0}..{rows[-1]}")
+        worst = max(worst, res["max_err_over_bound"])
+    return worst
+
+
 def tile_probe_rows(M: int, tile: int = 256, per_tile=(0, 1, 31, 32, 63, 64, 100, 127, 128, 191, 200, 255)):
     """Row indices that touch every workgroup tile row, every wave row and both
     halves of the 32-row MFMA blocks."""

@@ -242,11 +242,3 @@ def test_persistent_kernel_needs_an_even_number_of_k_steps():
     assert even.kernel == 3 and odd.kernel == 2 and odd.workgroups == 1024
 
 
-def test_stream_k_is_opt_in(monkeypatch):
-    d = P.make_desc()
-    assert _plan(d, 5120, 5120, 5120).kernel == 2      # 400 tiles: never chosen by the library itself
-    monkeypatch.setenv("PRISM_STREAMK", "1")
-    p = _plan(d, 5120, 5120, 5120)
-    assert p.kernel == 4 and p.workgroups == 256 and p.workspace_bytes == 4096 + 256 * 256 * 256 * 4
-    assert _plan(P.make_desc(split_k=1), 5120, 5120, 5120).kernel == 2   # only with the library's own split choice
-    assert _plan(d, 2048, 2048, 2048).kernel == 2      # fewer tiles than compute units

@@ -87,11 +87,11 @@ def test_empty_input_and_error_codes():
         P.scan_u32(x, x, 100, None)                       # no workspace
 
 
-def test_bounded_wait_gives_up_cleanly(monkeypatch):
+def test_bounded_wait_gives_up_cleanly(set_hook):
     """With a poll budget of zero a look-back that meets an unpublished tile gives up: the
     kernel still terminates, and either the result is right (nobody had to wait) or the
     error word says so."""
-    monkeypatch.setenv("PRISM_SCAN_SPIN_LIMIT", "0")
+    set_hook("PRISM_SCAN_SPIN_LIMIT", "0")
     n = 1500 * TILE
     x = scan_input_u32(11, n)
     d = torch.from_numpy(x.view(np.int32)).cuda()
