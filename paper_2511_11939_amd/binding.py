@@ -79,6 +79,9 @@ def load_library():
         return _lib
     if not os.path.exists(_build.LIB_PATH):
         _build.build()
+    elif _build.is_stale():
+        import warnings
+        warnings.warn("libprism_gemm.so is older than its sources: run paper_2511_11939_amd.build.build(force=True)")
     lib = ctypes.CDLL(_build.LIB_PATH)
     i64, vp, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
     dp = ctypes.POINTER(GemmDesc)
