@@ -273,9 +273,15 @@ def main() -> int:
 
     stream = torch.cuda.current_stream()
 
+    # one step = one call of the C entry point through the binding of the same name; the
+    # arguments are prepared once, so that the host adds as little as possible to the timed region
+    call = (desc, w.M, w.N, w.K, A.data_ptr(), w.lda(), w.M * w.K, B.data_ptr(), w.ldb(), w.K * w.N,
+            C.data_ptr(), w.N, w.M * w.N, w.batch, stream.cuda_stream)
+
     def step():
-        P.gemm(A, B, C, M=w.M, N=w.N, K=w.K, desc=desc, batch=w.batch, strideA=w.M * w.K,
-               strideB=w.K * w.N, strideC=w.M * w.N, stream=stream)
+        status = P.prism_gemm_batched(*call)
+        if status != 0:
+            raise P.PrismError(status, "prism_gemm_batched")
 
     def timed(warmup: int, steps: int):
         for _ in range(warmup):
@@ -287,6 +293,8 @@ def main() -> int:
         for _ in range(steps):
             step()
         ev1.record(stream)
+        while not ev1.query():      # poll for the end instead of sleeping on it: the wake-up of a blocked
+            pass                    # host thread would add some ten microseconds to the timed region
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ev0.elapsed_time(ev1)   # host wall seconds, device ms (events on the launch stream)
 
@@ -303,6 +311,32 @@ def main() -> int:
 
     ramp_launches = clock_ramp(step, args.ramp_seconds)
     wall, dev_ms = timed(args.warmup, args.steps)
+
+    in_kernel = None
+    if plan.kernel == 2:
+        # A few launches more, with time stamps from inside the kernel (prism_gemm_batched_stamped):
+        # how long the phases of a workgroup take and which shader clock the GPU sustains in the K loop.
+        stamps = torch.zeros(plan.workgroups * P.STAMP_BYTES_PER_WORKGROUP // 8, dtype=torch.int64, device="cuda")
+        for _ in range(3):
+            status = P.prism_gemm_batched_stamped(*call[:-1], stamps, stamps.numel() * 8, stream.cuda_stream)
+            assert status == 0, status
+        torch.cuda.synchronize()
+        st = stamps.cpu().numpy().reshape(-1, 4, 2).astype(np.float64)    # [workgroup, point, (cycles, 100 MHz ticks)]
+        d_cyc, d_us = np.diff(st[:, :, 0], axis=1), np.diff(st[:, :, 1], axis=1) / 100.0
+        k_steps = (w.K // (32 if w.ab_dtype == "f32" else 64)) / max(1, plan.split_k)
+        loop_clock = d_cyc[:, 1].sum() / d_us[:, 1].sum()
+        die_clock = [d_cyc[g::8, 1].sum() / d_us[g::8, 1].sum() for g in range(8) if st[g::8].size]
+        in_kernel = {
+            "k_loop_clock_mhz": round(loop_clock, 0), "k_loop_cycles_per_step": round(d_cyc[:, 1].mean() / k_steps, 1),
+            "k_loop_us_per_step": round(d_us[:, 1].mean() / k_steps, 4),
+            "us_entry_to_first_fragments": round(d_us[:, 0].mean(), 2), "us_k_loop": round(d_us[:, 1].mean(), 2),
+            "us_epilogue": round(d_us[:, 2].mean(), 2),
+            "us_first_entry_to_last_end": round((st[:, 3, 1].max() - st[:, 0, 1].min()) / 100.0, 2),
+            "die_k_loop_clock_mhz": [round(c, 0) for c in die_clock],
+            "peak_at_k_loop_clock_tflops": round(loop_clock * 1e6 * 256 * (256 if w.ab_dtype == "f32" else 4096) / 1e12, 1),
+            "what": "per-workgroup averages of one stamped launch; the peak at the K loop's clock is 256 compute units "
+                    "x FLOP per clock x the clock measured inside the K loop",
+        }
 
     ms_per_step = wall * 1e3 / args.steps
     tflops = w.flops / (ms_per_step * 1e-3) / 1e12
@@ -347,6 +381,8 @@ def main() -> int:
     }
     if probe is not None:
         out["mfma_probe"] = probe
+    if in_kernel is not None:
+        out["in_kernel"] = in_kernel
     if plan.split_k > 1:
         # A K split also moves the fp32 partial sums: written once by the slices, read once by
         # the reduction.  With them counted the path is bound by memory, not by the matrix pipe.

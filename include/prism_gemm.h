@@ -194,6 +194,26 @@ PRISM_API prism_status_t prism_mfma_probe(int32_t ab_dtype, const void* operands
                                           void* hip_stream);
 
 /*
+ * Measurement aid: prism_gemm_batched with time stamps.  The same launch (same kernel, same
+ * result), in which the first thread of every workgroup of the main kernel records, at four
+ * points, the shader-clock counter and the constant 100 MHz counter:
+ *   stamps[8*g + 2*p], stamps[8*g + 2*p + 1]   cycles, 100 MHz ticks of workgroup g at point p
+ *   p = 0 kernel entry, 1 first operand fragments in registers (start of the K loop),
+ *       2 K loop done, 3 results stored and acknowledged.
+ * Differences of cycles over differences of ticks give the clock the GPU sustained in a
+ * phase; workgroup g runs on die g % 8.  Only problems that prism_gemm_plan sends to the
+ * direct-to-LDS pipeline (plan.kernel == 2) can be stamped, others are PRISM_ERR_UNSUPPORTED.
+ * stamps: device, 8-byte aligned, plan.workgroups * PRISM_STAMP_BYTES_PER_WORKGROUP bytes or
+ * more (else PRISM_ERR_WORKSPACE).  Everything else as prism_gemm_batched.
+ */
+#define PRISM_STAMP_BYTES_PER_WORKGROUP ((size_t)64)
+PRISM_API prism_status_t prism_gemm_batched_stamped(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,
+                                          const void* A, int64_t lda, int64_t strideA,
+                                          const void* B, int64_t ldb, int64_t strideB,
+                                          void* C, int64_t ldc, int64_t strideC, int64_t batch,
+                                          uint64_t* stamps, size_t stamp_bytes, void* hip_stream);
+
+/*
  * Test aid: shows, on the device, the two lane layouts the kernels are built on, through the
  * very device functions the kernels use (one wavefront, a few microseconds).
  *

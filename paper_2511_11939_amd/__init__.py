@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     GemmDesc, GemmPlan, PrismError, Status, DType, Layout,
     load_library, library_path,
     prism_gemm, prism_gemm_batched, prism_gemm_workspace_size, prism_gemm_plan,
+    prism_gemm_batched_stamped, STAMP_BYTES_PER_WORKGROUP,
     prism_sched_map, prism_status_string, prism_version, prism_mfma_probe, prism_layout_probe, prism_reread_environment,
     LAYOUT_ACCUMULATOR_BF16, LAYOUT_ACCUMULATOR_F16, LAYOUT_K_ROWS_READ,
     MFMA_PROBE_OPERAND_BYTES, MFMA_PROBE_COUNTER_BYTES, MFMA_PROBE_FLOP_PER_ITERATION,

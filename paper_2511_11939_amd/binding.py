@@ -89,6 +89,8 @@ def load_library():
     lib.prism_gemm.restype = ctypes.c_int
     lib.prism_gemm_batched.argtypes = [dp, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, i64, vp]
     lib.prism_gemm_batched.restype = ctypes.c_int
+    lib.prism_gemm_batched_stamped.argtypes = [dp, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, i64, vp, sz, vp]
+    lib.prism_gemm_batched_stamped.restype = ctypes.c_int
     lib.prism_gemm_workspace_size.argtypes = [dp, i64, i64, i64, i64, ctypes.POINTER(sz)]
     lib.prism_gemm_workspace_size.restype = ctypes.c_int
     lib.prism_gemm_plan.argtypes = [dp, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, i64,
@@ -142,6 +144,16 @@ def prism_gemm_batched(desc, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, 
                        hip_stream=None) -> int:
     return load_library().prism_gemm_batched(_descp(desc), M, N, K, _p(A), lda, strideA, _p(B), ldb,
                                              strideB, _p(C), ldc, strideC, batch, _p(hip_stream))
+
+
+STAMP_BYTES_PER_WORKGROUP = 64
+
+
+def prism_gemm_batched_stamped(desc, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch,
+                               stamps, stamp_bytes, hip_stream=None) -> int:
+    return load_library().prism_gemm_batched_stamped(_descp(desc), M, N, K, _p(A), lda, strideA, _p(B), ldb,
+                                                     strideB, _p(C), ldc, strideC, batch, _p(stamps), stamp_bytes,
+                                                     _p(hip_stream))
 
 
 def prism_gemm_workspace_size(desc, M, N, K, batch=1):

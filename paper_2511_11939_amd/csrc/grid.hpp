@@ -7,6 +7,7 @@
 #pragma once
 
 #include "lane.hpp"
+#include "stamp.hpp"
 
 namespace prism {
 
@@ -32,6 +33,7 @@ struct GemmParams {
     int c_vec;            // 4-element groups of C (and of the bias) are vector-aligned
     int p_vec;            // 4-element groups of the split-K scratch are 16-byte aligned
     int c_vec8;           // 8-element groups of C (and of the bias) start on 16-byte boundaries
+    uint64_t* stamps;     // nullptr, or kStampWords uint64 per workgroup of the main kernel (measurement aid)
 };
 
 namespace grid {

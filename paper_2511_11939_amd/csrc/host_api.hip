@@ -326,6 +326,23 @@ prism_status_t prism_gemm_batched(const prism_gemm_desc_t* d, int64_t M, int64_t
     return run(pr, static_cast<hipStream_t>(hip_stream));
 }
 
+prism_status_t prism_gemm_batched_stamped(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K,
+                                          const void* A, int64_t lda, int64_t strideA, const void* B, int64_t ldb,
+                                          int64_t strideB, void* C, int64_t ldc, int64_t strideC, int64_t batch,
+                                          uint64_t* stamps, size_t stamp_bytes, void* hip_stream)
+{
+    Problem pr;
+    const prism_status_t s =
+        make_problem(d, M, N, K, A, lda, strideA, B, ldb, strideB, C, ldc, strideC, batch, true, &pr);
+    if (s != PRISM_OK) return s;
+    if (pr.plan.kernel != 2) return PRISM_ERR_UNSUPPORTED;  // only the pipelined kernel leaves stamps
+    if (!stamps || reinterpret_cast<uintptr_t>(stamps) % 8 != 0) return PRISM_ERR_INVALID_ARG;
+    if (stamp_bytes < static_cast<size_t>(pr.plan.workgroups) * PRISM_STAMP_BYTES_PER_WORKGROUP) return PRISM_ERR_WORKSPACE;
+    static_assert(PRISM_STAMP_BYTES_PER_WORKGROUP == prism::kStampWords * sizeof(uint64_t), "stamp layout");
+    pr.p.stamps = stamps;
+    return run(pr, static_cast<hipStream_t>(hip_stream));
+}
+
 prism_status_t prism_gemm(const prism_gemm_desc_t* d, int64_t M, int64_t N, int64_t K, const void* A,
                           int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, void* hip_stream)
 {

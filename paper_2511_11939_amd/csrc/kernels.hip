@@ -174,6 +174,7 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
     __shared__ __attribute__((aligned(1024))) char lds[P::LDS_BYTES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    stamp(p.stamps, STAMP_ENTRY);
     const Placement q = place<BM, BN>(p, blockIdx.x);
 
     constexpr int ES = P::ES;
@@ -188,7 +189,8 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
     typename P::tile_t acc;
     acc.clear();
     P::run(wgp, acc, a_tile, a_ld, a_rows, b_tile, b_ld, b_rows,
-           (q.k_end - q.k_begin) / P::K_PER_STEP, lds, wave, lane);
+           (q.k_end - q.k_begin) / P::K_PER_STEP, lds, wave, lane, p.stamps);
+    stamp(p.stamps, STAMP_K_LOOP_DONE);
 
     // The epilogue's per-lane addressing is computed after the K loop: kept live across it, it
     // would not fit in registers beside the accumulators and fragments.
@@ -196,6 +198,10 @@ __global__ __launch_bounds__(P::THREADS) void gemm_pipelined(const GemmParams p)
     asm volatile("" : "+v"(lane_now));
     epilogue<typename P::tile_t, P::MT, P::NT, false, P::PAIRED_N>(wgp, p, q, acc, q.m0 + (wave / WAVES_N) * P::WTM,
                                                                    q.n0 + (wave % WAVES_N) * P::WTN, lds, wave, lane_now);
+    if (p.stamps) {  // the last stamp is taken when this wave's stores have been acknowledged
+        wg::wait_counts<0, 0>();
+        stamp(p.stamps, STAMP_STORES_DONE);
+    }
 }
 
 // Persistent form for the 256x256x64 tile: workgroup w takes tiles w, w + gridDim.x, ...

@@ -15,6 +15,7 @@
 #include <type_traits>
 
 #include "lane.hpp"
+#include "stamp.hpp"
 #include "wave.hpp"
 
 namespace prism {
@@ -282,7 +283,7 @@ struct Pipeline {
     // has the next MFMA queued while the memory instructions issue.
     __device__ __forceinline__ static void run(persp::Workgroup wgp, tile_t& acc, const char* a_tile, uint32_t a_ld, int a_rows,
                                const char* b_tile, uint32_t b_ld, int b_rows, int ksteps,
-                               char* lds, int wave, int lane)
+                               char* lds, int wave, int lane, uint64_t* stamps = nullptr)
     {
         const persp::Wave wv = wgp.wave();  // every wave of the workgroup runs this code
         constexpr int PARTS = wave::mfma_parts(frag_t{});  // matrix instructions per block and sub-step
@@ -418,6 +419,7 @@ struct Pipeline {
 #pragma unroll
         for (int r = 0; r < NR; ++r) read(r, 0, 0, 0);
         PRISM_PARANOID_SYNC(wgp);
+        stamp(stamps, STAMP_FIRST_FRAGMENTS);
 
         // MFMA slots of the memory instructions of a group: reads on the even slots, copies on
         // the odd ones, so no MFMA has more than one of them in its 16-cycle shadow.
@@ -704,11 +706,16 @@ struct PersistentPipe {
         using slot0 = std::integral_constant<int, 0>;
         using slot1 = std::integral_constant<int, 1>;
         for (;;) {
-            // Without a following tile the copies past the end re-read this tile's first two
-            // steps into slots nobody reads again: no branch around any copy.
+            // Without a following tile the copies past the end re-read this tile's last two
+            // steps (just fetched, so they come from the cache) into slots nobody reads again:
+            // no branch around any copy and no traffic to memory.
             Source sn = sc;
             int next_ksteps = ksteps;
             const bool has_next = peek(sn, next_ksteps);
+            if (!has_next) {
+                sn.a = sc.a + static_cast<int64_t>(ksteps - 2) * L::kRowBytes;
+                sn.b = sc.b + static_cast<int64_t>(ksteps - 2) * L::kRowBytes;
+            }
             acc.clear();
             pin_acc();
             // Every tile has an even number of K steps, so a trip of two steps always starts on

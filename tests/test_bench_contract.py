@@ -79,6 +79,9 @@ def test_bench_prints_one_json_line_with_the_contract_keys(workload):
         assert d["cold"]["value"] > 0 and d["cold"]["ms_per_step"] > 0
         assert d["mfma_probe"]["tflops_loop"] > 0 and 500 < d["mfma_probe"]["clock_mhz"] < 3000
         assert roof["mfma_probe_tflops"] == d["mfma_probe"]["tflops_loop"]
+        # and with the clock the K loop itself ran at, from stamps taken inside the kernel
+        assert 500 < d["in_kernel"]["k_loop_clock_mhz"] < 3000 and len(d["in_kernel"]["die_k_loop_clock_mhz"]) == 8
+        assert 2048 <= d["in_kernel"]["k_loop_cycles_per_step"] < 4096
 
 
 @pytest.mark.gpu

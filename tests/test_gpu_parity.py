@@ -464,3 +464,31 @@ def test_seeded_sweep(case):
 ])
 def test_extreme_aspect_ratios(M, N, K, kw):
     _general_case(M, N, K, ints=True, **kw)
+
+
+def test_stamped_launch_gives_the_same_result_and_ordered_stamps():
+    """prism_gemm_batched_stamped is the same launch plus time stamps from inside the kernel."""
+    M, N, K = 1024, 768, 512
+    rng = np.random.default_rng(21)
+    a = to_dev(to_bf16_bits(rng.standard_normal(M * K).astype(np.float32)))
+    b = to_dev(to_bf16_bits(rng.standard_normal(N * K).astype(np.float32)))
+    desc = P.make_desc()
+    s, plan = P.prism_gemm_plan(desc, M, N, K, a, K, 0, b, K, 0, None, N, 0, 1)
+    assert s == 0 and plan.kernel == 2
+    c0, c1 = alloc_c(M * N, "bf16", fill=0), alloc_c(M * N, "bf16", fill=0)
+    P.gemm(a, b, c0, M=M, N=N, K=K, desc=desc)
+    stamps = torch.zeros(plan.workgroups * 8, dtype=torch.int64, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    args = (desc, M, N, K, a, K, 0, b, K, 0, c1, N, 0, 1)
+    assert P.prism_gemm_batched_stamped(*args, stamps, stamps.numel() * 8 - 8, stream) == P.Status.WORKSPACE
+    assert P.prism_gemm_batched_stamped(*args, None, 1 << 20, stream) == P.Status.INVALID_ARG
+    assert P.prism_gemm_batched_stamped(*args, stamps, stamps.numel() * 8, stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(c0, c1)
+    st = stamps.cpu().numpy().reshape(-1, 4, 2)
+    assert (st > 0).all()
+    assert (np.diff(st[:, :, 0], axis=1) > 0).all() and (np.diff(st[:, :, 1], axis=1) >= 0).all()   # cycles and ticks go forward
+    clock_mhz = np.diff(st[:, 1:3, 0], axis=1).sum() / np.diff(st[:, 1:3, 1], axis=1).sum() * 100.0
+    assert 500 < clock_mhz < 3000
+    # a problem that does not run on the pipelined kernel cannot be stamped
+    assert P.prism_gemm_batched_stamped(desc, 100, 90, 70, a, 70, 0, b, 70, 0, c1, 90, 0, 1, stamps, 1 << 20, stream) == P.Status.UNSUPPORTED
