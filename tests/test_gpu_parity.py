@@ -19,6 +19,11 @@ from gpu_harness import (run_workload, assert_matches_oracle, assert_every_entry
 
 pytestmark = pytest.mark.gpu
 
+# The whole file can be run with a kernel choice forced from outside (PRISM_PERSISTENT=1,
+# PRISM_GEMM_CONFIG=0 ...): the numeric checks then exercise that kernel and the assertions
+# about the library's own choice are skipped.
+FORCED = bool(os.environ.get("PRISM_PERSISTENT") or os.environ.get("PRISM_GEMM_CONFIG"))
+
 ENC = {"bf16": to_bf16_bits, "f16": to_f16_bits, "f32": lambda v: np.asarray(v, dtype=np.float32)}
 
 
@@ -78,7 +83,7 @@ def test_cfg2_every_entry_and_f32_cross_check():
     w = CONFIGS["cfg2_4096_bf16"]
     inp = make_inputs(w)
     c, plan = run_workload(w, inp)
-    assert plan["kernel"] == 2 and plan["split_k"] == 1
+    assert FORCED or (plan["kernel"] == 2 and plan["split_k"] == 1)
     assert_every_entry_matches_oracle(w, inp, c, what="bf16 out")
     # same launch with an fp32 result: strict bound, and the bf16 result is its rounding
     c32, _ = run_workload(w, inp, c_dtype="f32")
@@ -103,7 +108,7 @@ def test_cfg3_bias_every_entry():
     w = CONFIGS["cfg3_proj_bias"]
     inp = make_inputs(w)
     c, plan = run_workload(w, inp)
-    assert plan["kernel"] == 2
+    assert FORCED or plan["kernel"] == 2
     assert_every_entry_matches_oracle(w, inp, c)
 
 
@@ -144,7 +149,7 @@ def test_cfg5_batched_all_problems_every_entry():
     w = CONFIGS["cfg5_batched_512"]
     inp = make_inputs(w)
     c, plan = run_workload(w, inp)
-    assert plan["kernel"] == 3 and plan["workgroups"] == 256      # persistent over 1024 tiles
+    assert FORCED or (plan["kernel"] == 3 and plan["workgroups"] == 256)      # persistent over 1024 tiles
     for b in range(w.batch):
         assert_matches_oracle(w, inp, c, batch_index=b, what=f"problem {b}")
 
@@ -350,7 +355,7 @@ def test_tile_counts_that_leave_the_last_round_of_compute_units_partly_empty(M, 
     desc = P.make_desc(c_dtype="f32")
     s, plan = P.prism_gemm_plan(desc, M, N, K, None, K, 0, None, K, 0, None, N, 0, 1)
     tiles = plan.tiles_m * plan.tiles_n
-    assert s == 0 and plan.tile_m == 256 and tiles > 256 and tiles % 256 != 0
+    assert s == 0 and tiles > 256 and tiles % 256 != 0 and (FORCED or plan.tile_m == 256)
     _general_case(M, N, K, ints=True)
     _general_case(M, N, K, ab="f16", cd="bf16", bias=True, alpha=-1.25, seed=5)
     rng = np.random.default_rng(3)
