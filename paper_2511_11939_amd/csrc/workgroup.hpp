@@ -254,6 +254,11 @@ struct Pipeline {
     static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    // LDS: the A tiles of all slots first, then the B tiles.  A lane's fragment addresses are then
+    // one base per operand and sub-step plus constants below 64 KiB (block, slot), which fit the
+    // offset field of the LDS read: no address arithmetic inside the K loop.
+    static constexpr int a_slot(int stage) { return stage * A_BYTES; }
+    static constexpr int b_slot(int stage) { return STAGES * A_BYTES + stage * B_BYTES; }
     static constexpr int COPY_ROWS = 1024 / L::kRowBytes;  // rows moved by one wave-wide copy
     static constexpr int A_COPIES = BM / COPY_ROWS / NW, B_COPIES = BN / COPY_ROWS / NW;  // per wave per K step
     static constexpr int COPIES = A_COPIES + B_COPIES;
@@ -340,9 +345,13 @@ struct Pipeline {
             const int64_t k_bytes = static_cast<int64_t>(step) * L::kRowBytes;
             const int64_t a_bytes = A_MK ? static_cast<int64_t>(step) * K_PER_STEP * a_ld : k_bytes;
             const int64_t b_bytes = B_KN ? static_cast<int64_t>(step) * K_PER_STEP * b_ld : k_bytes;
-            const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(wv, a_tile + a_bytes, g_off[c], slot, c * NW * 1024);
-            else copy_async_16(wv, b_tile + b_bytes, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
+            // (the slot's offset goes into the instruction's constant when the slot is known at compile time,
+            // as in the steady loop, and into the base otherwise)
+            const char* src = c < A_COPIES ? a_tile + a_bytes : b_tile + b_bytes;
+            const int slot = c < A_COPIES ? a_slot(stage) : b_slot(stage);
+            const int in_slot = (c < A_COPIES ? c : c - A_COPIES) * NW * 1024;
+            if (__builtin_constant_p(stage)) copy_async_16(wv, src, g_off[c], lds0, slot + in_slot);
+            else copy_async_16(wv, src, g_off[c], lds0 + slot, in_slot);
         };
         // 16-bit operands kept as k-rows: fragments come from the transposing LDS read, see
         // wave::read_k_rows_half; four per-lane address parts serve all reads.
@@ -367,24 +376,32 @@ struct Pipeline {
         const int a_row0 = wave_m * WTM, b_row0 = wave_n * WTN;
         using v4s = wave::v4s;
         static_assert(WTM % 8 == 0 && WTN % 8 == 0 && lane::kBlock % 8 == 0, "row blocks start at multiples of 8 rows");
-        uint32_t frag_part[KSUB];  // the lane's share of a fragment address, one per sub-step
+        // The lane's share of a fragment address, one per operand and sub-step: wave tile's first
+        // row, the lane's row and chunk inside a block, and for B the start of the B tiles.  Every
+        // read of the K loop is one of these plus a constant (block, slot) below 64 KiB.
+        uint32_t fa_off[KSUB], fb_off[KSUB];
 #pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) frag_part[ks] = lane::fragment_lane_part<BK>(wv.lane(), ks, lane);
+        for (int ks = 0; ks < KSUB; ++ks) {
+            const uint32_t part = lane::fragment_lane_part<BK>(wv.lane(), ks, lane);
+            fa_off[ks] = a_row0 * L::kRowBytes + part;
+            fb_off[ks] = b_slot(0) + b_row0 * L::kRowBytes + part;
+            asm volatile("" : "+v"(fa_off[ks]), "+v"(fb_off[ks]));  // kept in registers, not re-derived per read
+        }
         frag_t fa[2][MT], fb[2][NT];
         v4s fah[2][MT][2], fbh[2][NT][2];  // operands kept as k-rows: the two halves of every fragment
         // read number r (0 .. NR-1) of sub-step ksub of slot `stage` into buffer `buf`;
         // order: a0, all b, remaining a -- what the first MFMAs of the next group need first
         auto read_a = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {  // x: fragment * A_READS + half
-            const char* st = lds + stage * STAGE_BYTES;
+            const char* st = lds + a_slot(stage);
             if constexpr (A_MK && ES == 2) fah[buf][x / 2][x % 2] = read_k_rows(st, a_row0, x / 2, ksub, x % 2);
             else if constexpr (A_MK) fa[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, a_row0 + lane::kBlock * x, ksub));
-            else fa[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + (a_row0 + lane::kBlock * x) * L::kRowBytes, frag_part[ksub]);
+            else fa[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + lane::kBlock * x * L::kRowBytes, fa_off[ksub]);
         };
         auto read_b = [&](int x, int buf, int stage, int ksub) __attribute__((always_inline)) {
-            const char* st = lds + stage * STAGE_BYTES + A_BYTES;
+            const char* st = lds + b_slot(stage);
             if constexpr (B_KN && ES == 2) fbh[buf][x / 2][x % 2] = read_k_rows(st, b_row0, x / 2, ksub, x % 2);
             else if constexpr (B_KN) fb[buf][x] = __builtin_bit_cast(frag_t, gather_k_rows(st, b_row0 + lane::kBlock * x, ksub));
-            else fb[buf][x] = lane::load_fragment_at<T>(wv.lane(), st + (b_row0 + lane::kBlock * x) * L::kRowBytes, frag_part[ksub]);
+            else fb[buf][x] = lane::load_fragment_at<T>(wv.lane(), st - b_slot(0) + lane::kBlock * x * L::kRowBytes, fb_off[ksub]);
         };
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
             if (r < A_READS) read_a(r, buf, stage, ksub);
@@ -575,6 +592,8 @@ struct PersistentPipe {
     static constexpr int WTM = 128, WTN = 128, MT = WTM / lane::kBlock, NT = WTN / lane::kBlock;
     static constexpr int KSUB = BK / lane::kBlockK, NM = MT * NT, NR = MT + NT;
     static constexpr int A_BYTES = BM * L::kRowBytes, B_BYTES = BN * L::kRowBytes, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int a_slot(int stage) { return stage * A_BYTES; }              // A tiles of both slots first,
+    static constexpr int b_slot(int stage) { return 2 * A_BYTES + stage * B_BYTES; }  // then the B tiles (see Pipeline)
     static constexpr int PATCH_BYTES = lane::kBlock * WTN * 4;
     static constexpr int PATCH_BASE = 2 * STAGE_BYTES;
     static constexpr int LDS_BYTES = PATCH_BASE + NW * PATCH_BYTES;
@@ -622,22 +641,30 @@ struct PersistentPipe {
                 const int rb = row_b < s.b_rows ? row_b : s.b_rows - 1;
                 g_off[i] = static_cast<uint32_t>(ra) * s.a_ld + chunk * lane::kChunkBytes;
                 g_off[A_COPIES + i] = static_cast<uint32_t>(rb) * s.b_ld + chunk * lane::kChunkBytes;
+                // (kept as they are in registers: left to itself the compiler splits every offset into a
+                // uniform and a per-lane part and adds them again in front of each copy of the K loop)
+                asm volatile("" : "+v"(g_off[i]), "+v"(g_off[A_COPIES + i]));
             }
         };
         // copy number c of the K step whose operands start at a_src / b_src, into slot `stage`
         auto copy = [&](int c, const char* a_src, const char* b_src, int stage) __attribute__((always_inline)) {
-            const uint32_t slot = lds0 + stage * STAGE_BYTES;
-            if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], slot, c * NW * 1024);
-            else copy_async_16(wv, b_src, g_off[c], slot, A_BYTES + (c - A_COPIES) * NW * 1024);
+            if (c < A_COPIES) copy_async_16(wv, a_src, g_off[c], lds0, a_slot(stage) + c * NW * 1024);
+            else copy_async_16(wv, b_src, g_off[c], lds0, b_slot(stage) + (c - A_COPIES) * NW * 1024);
         };
-        uint32_t frag_part[KSUB];  // the lane's share of a fragment address, one per sub-step
+        uint32_t fa_off[KSUB], fb_off[KSUB];  // the lane's share of a fragment address per operand and sub-step (see Pipeline)
 #pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) frag_part[ks] = lane::fragment_lane_part<BK>(wv.lane(), ks, lane);
+        for (int ks = 0; ks < KSUB; ++ks) {
+            const uint32_t part = lane::fragment_lane_part<BK>(wv.lane(), ks, lane);
+            fa_off[ks] = a_row0 * L::kRowBytes + part;
+            fb_off[ks] = b_slot(0) + b_row0 * L::kRowBytes + part;
+            asm volatile("" : "+v"(fa_off[ks]), "+v"(fb_off[ks]));
+        }
         auto read = [&](int r, int buf, int stage, int ksub) __attribute__((always_inline)) {
-            const char* st = lds + stage * STAGE_BYTES;
-            if (r == 0) fa[buf][0] = lane::load_fragment_at<T>(wv.lane(), st + a_row0 * L::kRowBytes, frag_part[ksub]);
-            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment_at<T>(wv.lane(), st + A_BYTES + (b_row0 + lane::kBlock * (r - 1)) * L::kRowBytes, frag_part[ksub]);
-            else fa[buf][r - NT] = lane::load_fragment_at<T>(wv.lane(), st + (a_row0 + lane::kBlock * (r - NT)) * L::kRowBytes, frag_part[ksub]);
+            const char* sa = lds + a_slot(stage);
+            const char* sb = lds + b_slot(stage) - b_slot(0);
+            if (r == 0) fa[buf][0] = lane::load_fragment_at<T>(wv.lane(), sa, fa_off[ksub]);
+            else if (r <= NT) fb[buf][r - 1] = lane::load_fragment_at<T>(wv.lane(), sb + lane::kBlock * (r - 1) * L::kRowBytes, fb_off[ksub]);
+            else fa[buf][r - NT] = lane::load_fragment_at<T>(wv.lane(), sa + lane::kBlock * (r - NT) * L::kRowBytes, fa_off[ksub]);
         };
         auto mfma = [&](int m, int buf) __attribute__((always_inline)) {
             const int i = m / NT, j = m % NT;
