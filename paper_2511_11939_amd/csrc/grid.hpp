@@ -45,17 +45,36 @@ struct TileCoord {
     int tile_m, tile_n, unit;
 };
 
+// floor(x / d) for 0 <= x, 1 <= d, both below 2^30.  On the device both must be the same in
+// every lane of the wave: the estimate from the reciprocal is moved to the scalar unit and
+// corrected there, which replaces the compiler's general expansion (four quarter-rate
+// integer multiplies per division, in front of a workgroup's first copies) by a handful of
+// full-rate instructions.  The correction loops make the result exact whatever the error of
+// the estimate, so host and device agree.
+__host__ __device__ inline int uniform_quotient(int x, int d)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    int q = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<float>(x) * __builtin_amdgcn_rcpf(static_cast<float>(d))));
+    int rest = x - q * d;
+    while (rest < 0) { --q; rest += d; }
+    while (rest >= d) { ++q; rest -= d; }
+    return __builtin_amdgcn_readfirstlane(q);  // stays on the scalar unit, and so does what is derived from it
+#else
+    return x / d;
+#endif
+}
+
 // Position r in the locality order -> tile: groups of kGroupRows tile rows, m fastest, so that
 // a contiguous run of positions is a compact block sharing few A and B panels.
 __host__ __device__ inline void tile_at(int r, int tiles_m, int tiles_n, int& tile_m, int& tile_n)
 {
     const int group_span = kGroupRows * tiles_n;
-    const int group = r / group_span;
+    const int group = uniform_quotient(r, group_span);
     const int first_m = group * kGroupRows;
     const int rows = tiles_m - first_m < kGroupRows ? tiles_m - first_m : kGroupRows;
-    const int in_group = r % group_span;
-    tile_m = first_m + in_group % rows;
-    tile_n = in_group / rows;
+    const int in_group = r - group * group_span;
+    tile_n = uniform_quotient(in_group, rows);
+    tile_m = first_m + in_group - tile_n * rows;
 }
 
 // The share of die `die` when `total` positions are dealt to the dies as contiguous runs
@@ -73,6 +92,7 @@ __host__ __device__ inline void die_run(int die, int total, int& first, int& cou
 // the workgroups resident on one die form a contiguous run of a tile order;
 // step 2 walks the tiles in groups of kGroupRows tile rows, m fastest, so that
 // such a run is a compact block sharing few A and B panels in that die's L2.
+// On the device `wg` must be uniform over the wave (a workgroup id is).
 __host__ __device__ inline TileCoord schedule(int wg, int tiles_m, int tiles_n, int units)
 {
     const int tiles = tiles_m * tiles_n;
@@ -80,8 +100,8 @@ __host__ __device__ inline TileCoord schedule(int wg, int tiles_m, int tiles_n, 
     die_run(wg % kDies, tiles * units, first, count);
     const int q = first + wg / kDies;
     TileCoord t;
-    t.unit = q / tiles;
-    tile_at(q % tiles, tiles_m, tiles_n, t.tile_m, t.tile_n);
+    t.unit = units == 1 ? 0 : uniform_quotient(q, tiles);
+    tile_at(q - t.unit * tiles, tiles_m, tiles_n, t.tile_m, t.tile_n);
     return t;
 }
 

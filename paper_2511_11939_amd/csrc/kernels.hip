@@ -36,12 +36,20 @@ __device__ __forceinline__ Placement place(const GemmParams& p, int wg)
 {
     const grid::TileCoord c = grid::schedule(wg, p.tiles_m, p.tiles_n, p.batch * p.split_k);
     Placement q;
-    q.batch = c.unit / p.split_k;
+    q.batch = p.split_k == 1 ? c.unit : grid::uniform_quotient(c.unit, p.split_k);
     q.slice = c.unit - q.batch * p.split_k;
     q.m0 = c.tile_m * BM;
     q.n0 = c.tile_n * BN;
     q.k_begin = q.slice * p.k_slice;
     q.k_end = q.k_begin + p.k_slice < p.K ? q.k_begin + p.k_slice : p.K;
+    // uniform values: held in scalar registers, so that the tile addresses derived from them
+    // are computed by the scalar unit
+    q.batch = __builtin_amdgcn_readfirstlane(q.batch);
+    q.slice = __builtin_amdgcn_readfirstlane(q.slice);
+    q.m0 = __builtin_amdgcn_readfirstlane(q.m0);
+    q.n0 = __builtin_amdgcn_readfirstlane(q.n0);
+    q.k_begin = __builtin_amdgcn_readfirstlane(q.k_begin);
+    q.k_end = __builtin_amdgcn_readfirstlane(q.k_end);
     return q;
 }
 

@@ -297,6 +297,8 @@ struct Pipeline {
         constexpr int NR = A_READS * MT + B_READS * NT;                // fragment reads per sub-step
         // -- per-lane copy offsets: wave-copy i moves row block (i*NW + wave) of COPY_ROWS rows;
         //    a lane fills one chunk position of one row with the logical chunk the swizzle wants.
+        // (row pitches in bytes stay below 2^24 and rows below 2^8 -- the host refuses larger
+        // pitches for this kernel -- so the full-rate 24-bit multiply gives the exact product)
         const int sub_row = lane / L::kChunksPerRow;
         const int chunk = (lane % L::kChunksPerRow) ^ L::swizzle(wave * COPY_ROWS + sub_row);
         uint32_t g_off[COPIES];
@@ -316,14 +318,14 @@ struct Pipeline {
             int c = (lane % KN_CHUNKS) ^ swz;
             const int last = (cols - 1) / PER_CHUNK;
             c = c < last ? c : last;
-            return static_cast<uint32_t>(k_row) * ld + c * lane::kChunkBytes;
+            return __umul24(static_cast<uint32_t>(k_row), ld) + c * lane::kChunkBytes;
         };
 #pragma unroll
         for (int i = 0; i < A_COPIES; ++i) {
             if constexpr (!A_MK) {
                 int row = (i * NW + wave) * COPY_ROWS + sub_row;
                 row = row < a_rows ? row : a_rows - 1;
-                g_off[i] = static_cast<uint32_t>(row) * a_ld + chunk * lane::kChunkBytes;
+                g_off[i] = __umul24(static_cast<uint32_t>(row), a_ld) + chunk * lane::kChunkBytes;
             } else {
                 g_off[i] = k_row_offset(i, a_ld, a_rows);
             }
@@ -333,7 +335,7 @@ struct Pipeline {
             if constexpr (!B_KN) {
                 int row = lane::paired_tile_row((i * NW + wave) * COPY_ROWS + sub_row);
                 row = row < b_rows ? row : b_rows - 1;
-                g_off[A_COPIES + i] = static_cast<uint32_t>(row) * b_ld + chunk * lane::kChunkBytes;
+                g_off[A_COPIES + i] = __umul24(static_cast<uint32_t>(row), b_ld) + chunk * lane::kChunkBytes;
             } else {
                 g_off[A_COPIES + i] = k_row_offset(i, b_ld, b_rows);
             }
@@ -353,6 +355,16 @@ struct Pipeline {
             if (__builtin_constant_p(stage)) copy_async_16(wv, src, g_off[c], lds0, slot + in_slot);
             else copy_async_16(wv, src, g_off[c], lds0 + slot, in_slot);
         };
+        // -- prologue, first part: fill the slots.  The copies go out before the addressing of the
+        //    fragment reads is worked out: that arithmetic then runs while the first bytes travel.
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s)
+            if (s < ksteps) {
+#pragma unroll
+                for (int c = 0; c < COPIES; ++c) copy(c, s, s);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+
         // 16-bit operands kept as k-rows: fragments come from the transposing LDS read, see
         // wave::read_k_rows_half; four per-lane address parts serve all reads.
         uint32_t k_rows_part[4];
@@ -422,13 +434,7 @@ struct Pipeline {
             acc.acc[i][j] = wave::mfma_part(wv, b, a, e, acc.acc[i][j]);
         };
 
-        // -- prologue: fill the slots, wait for step 0, fetch its first fragments
-#pragma unroll
-        for (int s = 0; s < STAGES; ++s)
-            if (s < ksteps) {
-#pragma unroll
-                for (int c = 0; c < COPIES; ++c) copy(c, s, s);
-            }
+        // -- prologue, second part: wait for step 0, fetch its first fragments
         if (ksteps >= STAGES) wait_counts<(STAGES - 1) * COPIES, 0>();
         else wait_counts<0, 0>();
         barrier(wgp);
@@ -639,8 +645,8 @@ struct PersistentPipe {
                 const int row = (i * NW + wave) * COPY_ROWS + sub_row, row_b = lane::paired_tile_row(row);
                 const int ra = row < s.a_rows ? row : s.a_rows - 1;
                 const int rb = row_b < s.b_rows ? row_b : s.b_rows - 1;
-                g_off[i] = static_cast<uint32_t>(ra) * s.a_ld + chunk * lane::kChunkBytes;
-                g_off[A_COPIES + i] = static_cast<uint32_t>(rb) * s.b_ld + chunk * lane::kChunkBytes;
+                g_off[i] = __umul24(static_cast<uint32_t>(ra), s.a_ld) + chunk * lane::kChunkBytes;
+                g_off[A_COPIES + i] = __umul24(static_cast<uint32_t>(rb), s.b_ld) + chunk * lane::kChunkBytes;
                 // (kept as they are in registers: left to itself the compiler splits every offset into a
                 // uniform and a per-lane part and adds them again in front of each copy of the K loop)
                 asm volatile("" : "+v"(g_off[i]), "+v"(g_off[A_COPIES + i]));
