@@ -53,11 +53,11 @@ def source_digest() -> str:
 # (two runs), each divided by the factor the same counter shows on a copy of known size
 # (--calibrate-copy).  Summaries under profiles/.  workload -> (bytes, digest of the sources).
 MEASURED_TRAFFIC: dict = {
-    "cfg2_4096_bf16": (236434420, "9432b282365855fe"),
-    "cfg3_proj_bias": (944714748, "9432b282365855fe"),
-    "cfg4_splitk_f16": (274159816, "9432b282365855fe"),   # main kernel + reduction
-    "cfg5_batched_512": (403145468, "9432b282365855fe"),
-    "scan_u32_2p28": (2156947334, "9432b282365855fe"),
+    "cfg2_4096_bf16": (235341111, "8635ac6915c82671"),
+    "cfg3_proj_bias": (940389196, "8635ac6915c82671"),
+    "cfg4_splitk_f16": (273008490, "8635ac6915c82671"),   # main kernel + reduction
+    "cfg5_batched_512": (403188998, "8635ac6915c82671"),
+    "scan_u32_2p28": (2157336864, "8635ac6915c82671"),
 }
 
 
