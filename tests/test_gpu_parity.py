@@ -381,6 +381,17 @@ def test_alpha_beta_bias(cd):
     _general_case(200, 136, 192, cd=cd, alpha=0.0, beta=2.0)
 
 
+@pytest.mark.parametrize("tiles_m,tiles_n,batch,split", [(1, 1, 1, 1), (2, 3, 1, 1), (3, 5, 1, 2), (5, 2, 3, 1), (6, 7, 2, 3),
+                                                         (7, 1, 1, 1), (9, 4, 1, 1), (4, 9, 5, 1), (13, 3, 1, 2)])
+def test_tile_placement_over_grid_shapes(tiles_m, tiles_n, batch, split, set_hook):
+    """Every workgroup works out its tile, problem and K slice with divisions by run-time
+    values (a last group of one, two or three tile rows; several units or one): integers come
+    out exact only when every tile of every unit is computed exactly once."""
+    set_hook("PRISM_GEMM_CONFIG", "1")        # 128x128 tiles
+    M, N, K = 128 * tiles_m - 5, 128 * tiles_n - 9, 64 * 2 * split
+    _general_case(M, N, K, ints=True, batch=batch, split_k=split if split > 1 else 0)
+
+
 @pytest.mark.parametrize("split", [2, 3, 5, 64])
 def test_forced_split_k(split):
     _general_case(256, 256, 1024, split_k=split, ints=True)
