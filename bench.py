@@ -338,6 +338,10 @@ def main() -> int:
             "what": "per-workgroup averages of one stamped launch; the peak at the K loop's clock is 256 compute units "
                     "x FLOP per clock x the clock measured inside the K loop",
         }
+        if plan.workgroups <= 256:   # one round of workgroups: every K loop runs at the same time
+            loop_tflops = w.flops / (d_us[:, 1].mean() * 1e-6) / 1e12
+            in_kernel["k_loop_tflops"] = round(loop_tflops, 1)
+            in_kernel["k_loop_frac_of_peak_at_its_clock"] = round(loop_tflops / in_kernel["peak_at_k_loop_clock_tflops"], 4)
 
     ms_per_step = wall * 1e3 / args.steps
     tflops = w.flops / (ms_per_step * 1e-3) / 1e12
