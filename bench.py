@@ -53,11 +53,11 @@ def source_digest() -> str:
 # (two runs), each divided by the factor the same counter shows on a copy of known size
 # (--calibrate-copy).  Summaries under profiles/.  workload -> (bytes, digest of the sources).
 MEASURED_TRAFFIC: dict = {
-    "cfg2_4096_bf16": (235341111, "8635ac6915c82671"),
-    "cfg3_proj_bias": (940389196, "8635ac6915c82671"),
-    "cfg4_splitk_f16": (273008490, "8635ac6915c82671"),   # main kernel + reduction
-    "cfg5_batched_512": (403188998, "8635ac6915c82671"),
-    "scan_u32_2p28": (2157336864, "8635ac6915c82671"),
+    "cfg2_4096_bf16": (235343672, "8635ac6915c82671"),
+    "cfg3_proj_bias": (940362501, "8635ac6915c82671"),
+    "cfg4_splitk_f16": (273008348, "8635ac6915c82671"),   # main kernel + reduction
+    "cfg5_batched_512": (403132326, "8635ac6915c82671"),
+    "scan_u32_2p28": (2157301187, "8635ac6915c82671"),
 }
 
 
@@ -80,10 +80,11 @@ def clock_ramp(step, seconds: float) -> int:
     return n
 
 
-def mfma_probe(ab_dtype: str, iterations: int, ramp_seconds: float, launches: int = 20) -> dict:
+def mfma_probe(ab_dtype: str, iterations: int, ramp_seconds: float, launches: int = 20):
     """The matrix instructions alone (prism_mfma_probe: the GEMM's wave tile on register-resident
     N(0,1) operands, `iterations` K steps per launch) under the same protocol as the GEMM: what they
-    sustain on this machine right now, and at which shader clock."""
+    sustain on this machine right now, and at which shader clock.  Returns the figures and the launch
+    (for a later reading of the package power)."""
     import numpy as np
     import torch
     import paper_2511_11939_amd as P
@@ -113,11 +114,66 @@ def mfma_probe(ab_dtype: str, iterations: int, ramp_seconds: float, launches: in
     cycles, ticks = float(c[:, 0].mean()), float(c[:, 1].mean())
     flop = P.MFMA_PROBE_FLOP_PER_ITERATION * iterations * (0.5 if ab_dtype == "f32" else 1.0)
     loop_s = ticks / 100e6
-    return {"tflops_loop": round(flop / loop_s / 1e12, 1), "tflops_launch": round(flop / launch_s / 1e12, 1),
-            "clock_mhz": round(cycles / ticks * 100.0, 0), "cycles_per_k_step": round(cycles / iterations, 1),
-            "iterations": iterations, "launch_us": round(launch_s * 1e6, 2),
-            "what": "matrix instructions only, N(0,1) operands in registers, 256 workgroups x 4 waves, "
-                    "after the same clock ramp; tflops_loop is inside the kernel's loop, tflops_launch per launch"}
+    out = {"tflops_loop": round(flop / loop_s / 1e12, 1), "tflops_launch": round(flop / launch_s / 1e12, 1),
+           "clock_mhz": round(cycles / ticks * 100.0, 0), "cycles_per_k_step": round(cycles / iterations, 1),
+           "iterations": iterations, "launch_us": round(launch_s * 1e6, 2),
+           "what": "matrix instructions only, N(0,1) operands in registers, 256 workgroups x 4 waves, "
+                   "after the same clock ramp; tflops_loop is inside the kernel's loop, tflops_launch per launch"}
+    return out, step
+
+
+def socket_power(step, seconds: float):
+    """Package power and per-die shader clocks as the system management tool reports them while
+    `step` is launched back to back for `seconds` (after the timed region, so the polling cannot
+    disturb it).  The tool runs as a child process; without it, or if it reports nothing, None."""
+    import re
+    import shutil
+    import statistics
+    import subprocess
+    import threading
+    import torch
+    tool = shutil.which("amd-smi")
+    if tool is None:
+        return None
+    reports, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                reports.append(subprocess.run([tool, "metric", "--power", "--clock"], capture_output=True,
+                                              text=True, timeout=10).stdout)
+            except Exception:
+                return
+
+    poller = threading.Thread(target=poll, daemon=True)
+    t0 = time.perf_counter()
+    poller.start()
+    launches = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(100):
+            step()
+        torch.cuda.synchronize()
+        launches += 100
+    stop.set()
+    poller.join(timeout=15)
+    late = reports[len(reports) // 2:]          # the tool's power figure is an average over about a second
+    watts = [float(x) for r in late for x in re.findall(r"SOCKET_POWER:\s*([0-9.]+)\s*W", r)]
+    if not watts:
+        return None
+    clocks = [int(x) for x in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)\s*MHz", late[-1])]
+    cap = None
+    try:
+        smi = shutil.which("rocm-smi")
+        if smi:
+            out = subprocess.run([smi, "--showmaxpower"], capture_output=True, text=True, timeout=10).stdout
+            m = re.search(r"Max Graphics Package Power \(W\):\s*([0-9.]+)", out)
+            cap = float(m.group(1)) if m else None
+    except Exception:
+        cap = None
+    return {"socket_power_w": round(statistics.median(watts), 0), "power_cap_w": cap,
+            "gfx_clock_mhz_per_die": clocks, "seconds": seconds, "launches": launches, "samples": len(watts),
+            "what": "amd-smi metric --power --clock polled while the step runs back to back after the timed region; "
+                    "the cap is rocm-smi --showmaxpower"}
 
 
 def copy_ceiling_gbs(n_bytes: int = 1 << 28, reps: int = 20) -> float:
@@ -229,6 +285,8 @@ def main() -> int:
     ap.add_argument("--ramp-seconds", type=float, default=0.3,
                     help="untimed launches of the same step before the warm-up steps, long enough for the "
                          "GPU's clock governor to reach its sustained state (0 = none)")
+    ap.add_argument("--no-power", dest="power", action="store_false",
+                    help="skip the package-power reading (a few seconds of extra launches with the management tool polled)")
     ap.add_argument("--no-mfma-probe", dest="mfma_probe", action="store_false",
                     help="skip the matrix-instructions-only probe that is reported beside MFMA-bound workloads")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
@@ -308,7 +366,7 @@ def main() -> int:
     probe = None
     if args.mfma_probe and w.name != "cfg5_batched_512" and w.name != "cfg1_256_rowrow_f32":
         es_k = 32 if w.ab_dtype == "f32" else 64
-        probe = mfma_probe(w.ab_dtype, max(1, w.K // es_k // max(1, plan.split_k)), args.ramp_seconds)
+        probe, probe_step = mfma_probe(w.ab_dtype, max(1, w.K // es_k // max(1, plan.split_k)), args.ramp_seconds)
 
     ramp_launches = clock_ramp(step, args.ramp_seconds)
     wall, dev_ms = timed(args.warmup, args.steps)
@@ -388,6 +446,14 @@ def main() -> int:
         out["mfma_probe"] = probe
     if in_kernel is not None:
         out["in_kernel"] = in_kernel
+    if args.power:   # after everything that is timed, so that seconds of full load do not precede it
+        power = socket_power(step, 3.0)
+        if power is not None:
+            out["power"] = power
+        if probe is not None:   # and what the package draws with the matrix pipes alone at work
+            reading = socket_power(probe_step, 2.0)
+            if reading is not None:
+                out["mfma_probe"]["socket_power_w"] = reading["socket_power_w"]
     if plan.split_k > 1:
         # A K split also moves the fp32 partial sums: written once by the slices, read once by
         # the reduction.  With them counted the path is bound by memory, not by the matrix pipe.

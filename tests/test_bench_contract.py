@@ -59,7 +59,8 @@ import pytest
 @pytest.mark.parametrize("workload", ["cfg2_4096_bf16", "cfg5_batched_512", "scan_u32_2p28"])
 def test_bench_prints_one_json_line_with_the_contract_keys(workload):
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", workload, "--steps", "3",
-                        "--warmup", "1", "--ramp-seconds", "0.05", "--cpu-rows", "64"],
+                        "--warmup", "1", "--ramp-seconds", "0.05", "--cpu-rows", "64"] +
+                       ([] if workload == "cfg2_4096_bf16" else ["--no-power"]),
                        capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
@@ -82,6 +83,10 @@ def test_bench_prints_one_json_line_with_the_contract_keys(workload):
         # and with the clock the K loop itself ran at, from stamps taken inside the kernel
         assert 500 < d["in_kernel"]["k_loop_clock_mhz"] < 3000 and len(d["in_kernel"]["die_k_loop_clock_mhz"]) == 8
         assert 2048 <= d["in_kernel"]["k_loop_cycles_per_step"] < 4096
+        assert 0.5 < d["in_kernel"]["k_loop_frac_of_peak_at_its_clock"] <= 1.0
+        # the package power, where the machine's management tool reports it
+        if "power" in d:
+            assert d["power"]["socket_power_w"] > 100 and d["power"]["samples"] >= 1
 
 
 @pytest.mark.gpu
