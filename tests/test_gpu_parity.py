@@ -508,3 +508,14 @@ def test_stamped_launch_gives_the_same_result_and_ordered_stamps():
     assert 500 < clock_mhz < 3000
     # a problem that does not run on the pipelined kernel cannot be stamped
     assert P.prism_gemm_batched_stamped(desc, 100, 90, 70, a, 70, 0, b, 70, 0, c1, 90, 0, 1, stamps, 1 << 20, stream) == P.Status.UNSUPPORTED
+
+
+def test_log_hook_names_the_launch(set_hook, capfd):
+    """PRISM_LOG=1: one line per launch on stderr with the problem, the kernel, the tile and the split."""
+    set_hook("PRISM_LOG", "1")
+    _general_case(256, 256, 2048, split_k=2, ints=True)
+    err = capfd.readouterr().err
+    lines = [ln for ln in err.splitlines() if ln.startswith("prism_gemm:")]
+    assert len(lines) == 1, err
+    assert "M=256 N=256 K=2048 batch=1" in lines[0] and "kernel=gemm_pipelined" in lines[0]
+    assert "split_k=2" in lines[0] and "tile=" in lines[0] and "workgroups=" in lines[0]
