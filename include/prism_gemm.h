@@ -15,9 +15,10 @@
  * All pointers named "device" are HIP device pointers owned by the caller; the
  * library never allocates or frees memory and keeps no mutable global state
  * apart from its experiment hooks, read once from the environment (see
- * prism_reread_environment).  It is written for one MI355X: 256 compute units in 8 dies.  Calls enqueue work on the given HIP
- * stream and return without synchronising; every buffer must stay valid until
- * the stream has executed the work.  Calls are re-entrant.  Every argument
+ * prism_reread_environment).  It is written for one MI355X: 256 compute
+ * units in 8 dies.  Calls enqueue work on the given HIP stream and return
+ * without synchronising; every buffer must stay valid until the stream has
+ * executed the work.  Calls are re-entrant.  Every argument
  * error is detected on the host before anything is launched and reported as
  * a status code; the library never throws or aborts.
  */
