@@ -53,11 +53,11 @@ def source_digest() -> str:
 # (two runs), each divided by the factor the same counter shows on a copy of known size
 # (--calibrate-copy).  Summaries under profiles/.  workload -> (bytes, digest of the sources).
 MEASURED_TRAFFIC: dict = {
-    "cfg2_4096_bf16": (235343672, "8635ac6915c82671"),
-    "cfg3_proj_bias": (940362501, "8635ac6915c82671"),
-    "cfg4_splitk_f16": (273008348, "8635ac6915c82671"),   # main kernel + reduction
-    "cfg5_batched_512": (403132326, "8635ac6915c82671"),
-    "scan_u32_2p28": (2157301187, "8635ac6915c82671"),
+    "cfg2_4096_bf16": (235343597, "8635ac6915c82671"),
+    "cfg3_proj_bias": (940361503, "8635ac6915c82671"),
+    "cfg4_splitk_f16": (273008576, "8635ac6915c82671"),   # main kernel + reduction
+    "cfg5_batched_512": (403201246, "8635ac6915c82671"),
+    "scan_u32_2p28": (2157273466, "8635ac6915c82671"),
 }
 
 
